@@ -1,0 +1,255 @@
+"""ctypes front end of the CPU oracle (stq_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this module.  It holds argument marshalling and nothing of the method itself:
+every number comes out of the plain C in stq_oracle.c, which is compiled here
+with gcc (fp32, no fused multiply-add, no fast-math).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "stq_oracle.c")
+_LIB = os.path.join(_HERE, "libstq_oracle.so")
+
+CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+          "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile stq_oracle.c into libstq_oracle.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class Stats(C.Structure):
+    _fields_ = [
+        ("count", C.c_uint64),
+        ("g_sum", C.c_double), ("g_abs_sum", C.c_double), ("g_sq_sum", C.c_double), ("g_absmax", C.c_float),
+        ("m_sum", C.c_double), ("m_sq_sum", C.c_double), ("m_err_sq", C.c_double), ("m_absmax", C.c_float),
+        ("v_sum", C.c_double), ("v_sq_sum", C.c_double), ("v_err_sq", C.c_double), ("v_absmax", C.c_float),
+    ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class HParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("step", C.c_uint32)]
+
+
+class Ema(C.Structure):
+    _fields_ = [("n_ema", C.c_double), ("r_ema", C.c_double), ("v_ema", C.c_double)]
+
+
+class DecideCfg(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("tau", C.c_double), ("phi", C.c_double), ("eps", C.c_double),
+                ("v_offset", C.c_double), ("r_mode", C.c_int), ("n_thr", C.c_int),
+                ("thr", C.POINTER(C.c_double)), ("bits", C.POINTER(C.c_uint8))]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.stq_oracle_G.restype = C.c_float
+        L.stq_oracle_G.argtypes = [C.c_int]
+        for f in (L.stq_oracle_R, L.stq_oracle_L, L.stq_oracle_T):
+            f.restype = C.c_float
+            f.argtypes = [C.c_int, C.c_int]
+        L.stq_oracle_quant_linear_block.restype = C.c_float
+        L.stq_oracle_quant_linear_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.stq_oracle_quant_log_block.restype = C.c_float
+        L.stq_oracle_quant_log_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.stq_oracle_dequant_linear_block.restype = None
+        L.stq_oracle_dequant_linear_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]
+        L.stq_oracle_dequant_log_block.restype = None
+        L.stq_oracle_dequant_log_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]
+        L.stq_oracle_step.restype = None
+        L.stq_oracle_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_int, C.c_int, C.c_int, C.POINTER(HParams), C.POINTER(Stats)]
+        L.stq_oracle_code_words.restype = C.c_uint64
+        L.stq_oracle_code_words.argtypes = [C.c_uint64, C.c_int]
+        L.stq_oracle_pack.restype = None
+        L.stq_oracle_pack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_void_p]
+        L.stq_oracle_unpack.restype = None
+        L.stq_oracle_unpack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_void_p]
+        L.stq_oracle_repack.restype = None
+        L.stq_oracle_repack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        L.stq_oracle_decide.restype = None
+        L.stq_oracle_decide.argtypes = [C.POINTER(Ema), C.POINTER(Stats), C.c_int, C.POINTER(DecideCfg),
+                                        C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a, dtype):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags.c_contiguous, (a.dtype, dtype)
+    return a
+
+
+# ---------------------------------------------------------------- tables
+def G(j: int) -> np.float32:
+    return np.float32(lib().stq_oracle_G(j))
+
+
+def R(b: int, u: int) -> np.float32:
+    return np.float32(lib().stq_oracle_R(b, u))
+
+
+def Lv(b: int, c: int) -> np.float32:
+    return np.float32(lib().stq_oracle_L(b, c))
+
+
+def T(b: int, k: int) -> np.float32:
+    return np.float32(lib().stq_oracle_T(b, k))
+
+
+# ------------------------------------------------------------ quantizers
+def quant_linear_block(x: np.ndarray, b: int):
+    x = _chk(np.ascontiguousarray(x, dtype=np.float32), np.float32)
+    u = np.empty(x.size, np.uint8)
+    s = lib().stq_oracle_quant_linear_block(_p(x), x.size, b, _p(u))
+    return u, np.float32(s)
+
+
+def quant_log_block(x: np.ndarray, b: int):
+    x = _chk(np.ascontiguousarray(x, dtype=np.float32), np.float32)
+    c = np.empty(x.size, np.uint8)
+    s = lib().stq_oracle_quant_log_block(_p(x), x.size, b, _p(c))
+    return c, np.float32(s)
+
+
+def dequant_linear_block(u: np.ndarray, b: int, s) -> np.ndarray:
+    u = _chk(np.ascontiguousarray(u, dtype=np.uint8), np.uint8)
+    x = np.empty(u.size, np.float32)
+    lib().stq_oracle_dequant_linear_block(_p(u), u.size, b, C.c_float(float(s)), _p(x))
+    return x
+
+
+def dequant_log_block(c: np.ndarray, b: int, s) -> np.ndarray:
+    c = _chk(np.ascontiguousarray(c, dtype=np.uint8), np.uint8)
+    x = np.empty(c.size, np.float32)
+    lib().stq_oracle_dequant_log_block(_p(c), c.size, b, C.c_float(float(s)), _p(x))
+    return x
+
+
+# ------------------------------------------------------------------ state
+@dataclass
+class State:
+    """Unpacked optimizer state of one tensor: codes (one byte each) + block scales."""
+    numel: int
+    K: int
+    bm: int
+    bv: int
+    um: np.ndarray = field(default=None)
+    sm: np.ndarray = field(default=None)
+    cv: np.ndarray = field(default=None)
+    sv: np.ndarray = field(default=None)
+
+    @property
+    def nblocks(self):
+        return (self.numel + self.K - 1) // self.K
+
+    @staticmethod
+    def zeros(numel: int, K: int, bm: int, bv: int) -> "State":
+        """Alg. 1 initial state m_0 = v_0 = 0: linear zero code is qmax, log blocks have scale 0."""
+        nb = (numel + K - 1) // K
+        qmax = (1 << (bm - 1)) - 1
+        return State(numel, K, bm, bv,
+                     um=np.full(numel, qmax, np.uint8), sm=np.zeros(nb, np.float32),
+                     cv=np.zeros(numel, np.uint8), sv=np.zeros(nb, np.float32))
+
+    def copy(self):
+        return State(self.numel, self.K, self.bm, self.bv, self.um.copy(), self.sm.copy(),
+                     self.cv.copy(), self.sv.copy())
+
+
+def step(param: np.ndarray, grad: np.ndarray, st: State, *, lr, beta1, beta2, eps, weight_decay, t,
+         want_stats: bool = False):
+    """In-place Adam step of one tensor.  grad is float32, or uint16 holding bf16 bit patterns."""
+    _chk(param, np.float32)
+    assert param.size == st.numel and grad.size == st.numel
+    bf16 = grad.dtype == np.uint16
+    if not bf16:
+        _chk(grad, np.float32)
+    assert grad.flags.c_contiguous
+    hp = HParams(lr, beta1, beta2, eps, weight_decay, t)
+    stats = Stats() if want_stats else None
+    lib().stq_oracle_step(_p(param), _p(grad), int(bf16), st.numel, _p(st.um), _p(st.sm), _p(st.cv), _p(st.sv),
+                          st.bm, st.bv, st.K, C.byref(hp), C.byref(stats) if want_stats else None)
+    return stats
+
+
+# ----------------------------------------------------------------- layout
+def code_words(numel: int, b: int) -> int:
+    return int(lib().stq_oracle_code_words(numel, b))
+
+
+def pack(codes: np.ndarray, b: int) -> np.ndarray:
+    codes = _chk(np.ascontiguousarray(codes, dtype=np.uint8), np.uint8)
+    w = np.empty(code_words(codes.size, b), np.uint32)
+    lib().stq_oracle_pack(_p(codes), codes.size, b, _p(w))
+    return w
+
+
+def unpack(words: np.ndarray, numel: int, b: int) -> np.ndarray:
+    words = _chk(np.ascontiguousarray(words, dtype=np.uint32), np.uint32)
+    assert words.size >= code_words(numel, b)
+    c = np.empty(numel, np.uint8)
+    lib().stq_oracle_unpack(_p(words), numel, b, _p(c))
+    return c
+
+
+def pad_scales(s: np.ndarray, numel: int, K: int) -> np.ndarray:
+    """Scales as stored: zero-padded to 2048/K entries per 2048-element tile."""
+    tiles = (numel + 2047) // 2048
+    out = np.zeros(tiles * (2048 // K), np.float32)
+    out[: s.size] = s
+    return out
+
+
+def repack(codes: np.ndarray, state: int, b_old: int, b_new: int) -> np.ndarray:
+    codes = _chk(np.ascontiguousarray(codes, dtype=np.uint8), np.uint8)
+    out = np.empty_like(codes)
+    lib().stq_oracle_repack(_p(codes), codes.size, state, b_old, b_new, _p(out))
+    return out
+
+
+# --------------------------------------------------------------- decision
+PAPER_THRESHOLDS = (6.8, 12.0, 24.0)
+PAPER_BITS = (4, 8, 16, 32)
+PAPER_PHI = 7.2
+
+
+def decide(ema: Ema, stats: list, step_t: int, *, alpha=0.1, tau=1000.0, phi=PAPER_PHI, eps=1e-12,
+           v_offset=0.0, r_mode=0, thr=PAPER_THRESHOLDS, bits=PAPER_BITS):
+    L = len(stats)
+    arr = (Stats * L)(*stats)
+    thr_a = (C.c_double * len(thr))(*thr)
+    bits_a = (C.c_uint8 * len(bits))(*bits)
+    assert len(bits) == len(thr) + 1
+    cfg = DecideCfg(alpha, tau, phi, eps, v_offset, r_mode, len(thr), thr_a, bits_a)
+    bm = np.empty(L, np.uint8)
+    bv = np.empty(L, np.uint8)
+    sc = np.empty(L, np.float64)
+    lib().stq_oracle_decide(C.byref(ema), arr, L, C.byref(cfg), step_t, _p(bm), _p(bv), _p(sc))
+    return bm, bv, sc
