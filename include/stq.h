@@ -1,0 +1,168 @@
+/*
+ * stq.h -- C ABI of the MI355X (gfx950) quantized Adam step of STQuant.
+ *
+ * The library implements the per-layer loop body of the paper's Algorithm 1
+ * (moment update, block-wise Quantize of m [linear symmetric] and v
+ * [logarithmic] per Section 3.5, bias correction of the quantized moments,
+ * decoupled-weight-decay update), the per-layer statistics the Score Engine of
+ * Section 3.3 consumes, the conversion of stored codes when Map (Section 3.4)
+ * changes a layer's bit-width, and the host-side decision itself.
+ *
+ * Conventions
+ *   - Every function returns STQ_OK (0) or a negative STQ_E* code.  Nothing
+ *     throws, aborts or prints.  stq_strerror() names a code.
+ *   - "device" pointers are HIP device memory on the context's GPU, owned by the
+ *     caller; the library never allocates or frees per call.  "host" pointers
+ *     are ordinary process memory.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     stq_zero_state, stq_step and stq_repack are asynchronous on that stream;
+ *     stq_stats synchronises it.
+ *   - One context serves one stream at a time.  Calls on one context must not
+ *     overlap from several host threads.
+ *
+ * Storage of one state (m or v) of a tensor of `numel` elements, block K, width b:
+ *   codes : tiles of 2048 elements, 64*b 32-bit words per tile.  Inside a tile,
+ *           "lane" j (0..63) owns elements tile*2048 + 256*i + 4*j + e (i=0..7,
+ *           e=0..3) and writes their codes in the order n = 4*i+e, LSB first,
+ *           into a stream of 32*b bits; word p of that stream is stored at word
+ *           index tile*64*b + p*64 + j.  Pad elements (>= numel) have code bits 0.
+ *   scales: fp32, one per block of K consecutive elements, zero-padded to
+ *           2048/K entries per tile.
+ *   stq_state_bytes() returns both sizes.  Both arrays must be 256-byte aligned.
+ *   Values: first moment  m = scale * (u - qmax)/qmax,  qmax = 2^(b-1)-1, u = code;
+ *           second moment v = scale * 2^(-(2^b-1-c) * 2^(4-b)),  c = code.
+ */
+#ifndef STQ_H
+#define STQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  STQ_OK = 0,
+  STQ_EINVAL = -1,  /* null pointer, zero size, count above the context's limit */
+  STQ_EALIGN = -2,  /* a device buffer is not aligned as required */
+  STQ_EBITS = -3,   /* a width outside 2..8 */
+  STQ_EBLOCK = -4,  /* block size not 64, 128 or 256 */
+  STQ_EDEVICE = -5, /* no such device, or not a gfx950 GPU */
+  STQ_EHIP = -6,    /* a HIP runtime call failed */
+  STQ_ESTATE = -7   /* stq_stats called with nothing accumulated for that many tensors */
+};
+
+typedef struct stq_ctx stq_ctx; /* opaque, owned by the library */
+
+/* One parameter tensor = one "layer" l of Algorithm 1. */
+typedef struct {
+  void* param;        /* device, fp32[numel], 16-byte aligned, updated in place            */
+  const void* grad;   /* device, fp32[numel] or bf16[numel] (hparams.grad_dtype), 16-byte aligned */
+  uint64_t numel;     /* N_l >= 1                                                           */
+  void* m_codes;      /* device, first-moment codes, size from stq_state_bytes, in place    */
+  float* m_scales;    /* device, first-moment block scales, in place                        */
+  void* v_codes;      /* device, second-moment codes                                        */
+  float* v_scales;    /* device, second-moment block scales                                 */
+} stq_tensor;
+
+/* bit_plan[l]: the widths b_{l,t} of layer l's two states, each in 2..8. */
+typedef struct { uint8_t m_bits, v_bits; } stq_bits;
+
+/* Inputs of Algorithm 1 that the step needs. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay; /* eta, beta1, beta2, epsilon, lambda        */
+  uint32_t step;       /* t >= 1, used for the bias corrections 1 - beta^t                */
+  uint32_t block;      /* block size K: 64, 128 or 256                                    */
+  uint32_t grad_dtype; /* 0 = fp32, 1 = bf16                                              */
+  uint32_t flags;      /* bit 0: accumulate the per-layer statistics during this step     */
+} stq_hparams;
+#define STQ_FLAG_STATS 1u
+
+/* Host copy of one layer's accumulated statistics (Section 3.3 inputs plus the
+ * moments' own statistics and quantization error).  m and v are the new moments
+ * BEFORE quantization; *_err_sq is the sum of (x - Quantized(x))^2. */
+typedef struct {
+  uint64_t count;
+  double g_sum, g_abs_sum, g_sq_sum; float g_absmax;
+  double m_sum, m_sq_sum, m_err_sq;  float m_absmax;
+  double v_sum, v_sq_sum, v_err_sq;  float v_absmax;
+} stq_layer_stats;
+
+/* The O(1) state of the decision: the three global EMAs of Eq. 4 / Section 3.3.3. */
+typedef struct { double n_ema, r_ema, v_ema; } stq_decide_state;
+
+/* Parameters of the decision.  The paper's values: phi = 7.2, thr = {6.8, 12, 24},
+ * bits = {4, 8, 16, 32}; alpha, tau and eps are not given there.  Only widths
+ * 2..8 can be stored by this library; stq_decide itself maps to whatever `bits`
+ * holds.  `bits` has n_thr+1 entries: width = bits[#{i : thr[i] <= score}].  The
+ * second-moment width is mapped from score + v_offset. */
+typedef struct {
+  double alpha, tau, phi, eps, v_offset;
+  uint32_t flags;  /* bit 0: r_l = sigma(g)/(E|g|+eps) as in Algorithm 1 instead of Eq. 3's CV of |g| */
+  uint32_t n_thr;
+  const double* thr;   /* host, ascending */
+  const uint8_t* bits; /* host */
+} stq_decide_cfg;
+#define STQ_DECIDE_R_ALG1 1u
+
+/* Create a context on HIP device `device` (must be gfx950) for up to
+ * max_tensors tensors per call.  Builds the level/threshold tables of the two
+ * quantizers and allocates the descriptor and statistics buffers. */
+int stq_init(stq_ctx** out, int device, uint32_t max_tensors);
+
+/* Synchronise the device and free everything the context owns. */
+int stq_destroy(stq_ctx* ctx);
+
+/* Sizes in bytes of the code and scale arrays of one state (see "Storage"). Host only. */
+int stq_state_bytes(uint64_t numel, uint32_t block, uint32_t bits,
+                    uint64_t* code_bytes, uint64_t* scale_bytes);
+
+/* Write Algorithm 1's initial state m_0 = v_0 = 0 into the n tensors' code and
+ * scale arrays at the widths of bit_plan (param and grad are not touched and
+ * may be NULL). */
+int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
+                   const stq_bits* bit_plan, uint32_t block, void* hip_stream);
+
+/* One quantized Adam step over n tensors (Algorithm 1, the "for each layer"
+ * body, with the stored states as m_{t-1}, v_{t-1}): params, codes and scales
+ * are updated in place; with STQ_FLAG_STATS the statistics of tensor l are
+ * added to accumulator l.  tensors and bit_plan are host arrays of n entries,
+ * read before the call returns.  One kernel launch, no host synchronisation. */
+int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
+             const stq_bits* bit_plan, const stq_hparams* hp, void* hip_stream);
+
+/* Copy accumulators 0..n-1 to `out` (host, n entries), synchronise, and clear
+ * them on the device.  Sums are order-dependent in the last bits; the maxima
+ * are exact. */
+int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* hip_stream);
+
+/* Convert the codes of one state of one tensor from src_bits to dst_bits after
+ * Map changed the layer's width.  state: 0 = first moment, 1 = second moment.
+ * Code-domain conversion: the new code is the one the dst_bits quantizer gives
+ * the old code's value in a block of scale 1; the scales array is shared by
+ * both widths and is not touched.  src and dst must not overlap. */
+int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state,
+               const void* src_codes, uint32_t src_bits,
+               void* dst_codes, uint32_t dst_bits, void* hip_stream);
+
+/* Host-side bit-width decision for n layers (Algorithm 1, the "if t mod U = 0
+ * or t < 5" body; Eq. 2, 3, 4, 7, 8; Section 3.4 score and Map): updates *ema and
+ * writes plan_out[l].  score_out (host, n doubles) may be NULL.  Linear in n. */
+int stq_decide(stq_decide_state* ema, const stq_layer_stats* stats, uint32_t n,
+               const stq_decide_cfg* cfg, uint32_t step, stq_bits* plan_out,
+               double* score_out);
+
+/* The library's own quantizer tables, for inspection (host only, no context):
+ *   which 0: G[j] = fl32(2^(-j/32)), j < 511 (bits ignored)
+ *   which 1: first-moment values R_b[u], u < 2^b - 1
+ *   which 2: second-moment values L_b[c], c < 2^b
+ *   which 3: second-moment thresholds T_b[k], k < 2^b - 1
+ * Writes at most n floats to out and returns the table's length, or a negative code. */
+int stq_table(int which, uint32_t bits, float* out, uint32_t n);
+
+const char* stq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STQ_H */

@@ -1,0 +1,319 @@
+// Host side of the C ABI declared in include/stq.h: argument checks, the device-resident
+// tensor table, kernel launches, statistics read-back.  Compiled by hipcc (HIP runtime calls).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "stq.h"
+#include "stq_device.h"
+#include "stq_tables.h"
+
+using namespace stq;
+
+namespace {
+constexpr int kRing = 4;  // pinned staging slots for descriptor uploads
+}
+
+struct stq_ctx {
+  int device = -1;
+  uint32_t max_tensors = 0;
+  uint32_t n_cu = 0;
+  uint32_t groups_per_cu = 2;
+  uint32_t* d_tables = nullptr;
+  TensorDesc* d_desc = nullptr;
+  double* d_stats = nullptr;
+  TensorDesc* h_stage[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
+  hipEvent_t stage_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  int ring_pos = 0;
+  double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
+  std::vector<TensorDesc> uploaded;          // what d_desc currently holds
+  std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
+};
+
+namespace {
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_bits(uint32_t b) { return (b >= 2 && b <= 8) ? STQ_OK : STQ_EBITS; }
+
+int lg_block(uint32_t K) {
+  switch (K) { case 64: return 6; case 128: return 7; case 256: return 8; default: return -1; }
+}
+
+struct DeviceGuard {  // makes the context's device current for the duration of a call
+  int prev = -1; bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() { if (ok && prev >= 0) (void)hipSetDevice(prev); }
+};
+
+int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
+                bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles) {
+  if (!ctx || !t || !plan || n == 0 || n > ctx->max_tensors) return STQ_EINVAL;
+  if (lg_block(K) < 0) return STQ_EBLOCK;
+  out.resize(n);
+  uint64_t tiles = 0;
+  for (uint32_t l = 0; l < n; ++l) {
+    if (int e = check_bits(plan[l].m_bits)) return e;
+    if (int e = check_bits(plan[l].v_bits)) return e;
+    if (t[l].numel == 0) return STQ_EINVAL;
+    if (!t[l].m_codes || !t[l].m_scales || !t[l].v_codes || !t[l].v_scales) return STQ_EINVAL;
+    if (need_param_grad && (!t[l].param || !t[l].grad)) return STQ_EINVAL;
+    if (!aligned(t[l].m_codes, 256) || !aligned(t[l].m_scales, 256) || !aligned(t[l].v_codes, 256) ||
+        !aligned(t[l].v_scales, 256))
+      return STQ_EALIGN;
+    if (need_param_grad && (!aligned(t[l].param, 16) || !aligned(t[l].grad, 16))) return STQ_EALIGN;
+    const uint64_t nt = (t[l].numel + kTile - 1) / kTile;
+    if (tiles + nt > 0xFFFFFFFFull) return STQ_EINVAL;
+    TensorDesc& d = out[l];
+    d.param = static_cast<float*>(t[l].param);
+    d.grad = t[l].grad;
+    d.m_codes = static_cast<uint32_t*>(t[l].m_codes);
+    d.m_scales = t[l].m_scales;
+    d.v_codes = static_cast<uint32_t*>(t[l].v_codes);
+    d.v_scales = t[l].v_scales;
+    d.numel = t[l].numel;
+    d.tile_begin = static_cast<uint32_t>(tiles);
+    d.n_tiles = static_cast<uint32_t>(nt);
+    d.bm = plan[l].m_bits;
+    d.bv = plan[l].v_bits;
+    tiles += nt;
+  }
+  *total_tiles = static_cast<uint32_t>(tiles);
+  return STQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* stq_strerror(int code) {
+  switch (code) {
+    case STQ_OK: return "ok";
+    case STQ_EINVAL: return "invalid argument";
+    case STQ_EALIGN: return "misaligned device buffer";
+    case STQ_EBITS: return "bit-width outside 2..8";
+    case STQ_EBLOCK: return "block size must be 64, 128 or 256";
+    case STQ_EDEVICE: return "device missing or not gfx950";
+    case STQ_EHIP: return "HIP runtime error";
+    case STQ_ESTATE: return "no statistics accumulated";
+    default: return "unknown error";
+  }
+}
+
+int stq_state_bytes(uint64_t numel, uint32_t block, uint32_t bits, uint64_t* code_bytes,
+                    uint64_t* scale_bytes) {
+  if (numel == 0 || (!code_bytes && !scale_bytes)) return STQ_EINVAL;
+  if (lg_block(block) < 0) return STQ_EBLOCK;
+  if (int e = check_bits(bits)) return e;
+  const uint64_t tiles = (numel + kTile - 1) / kTile;
+  if (code_bytes) *code_bytes = tiles * 64ull * bits * 4ull;
+  if (scale_bytes) *scale_bytes = tiles * (kTile / block) * 4ull;
+  return STQ_OK;
+}
+
+int stq_table(int which, uint32_t bits, float* out, uint32_t n) {
+  if (!out) return STQ_EINVAL;
+  if (which == 0) {
+    for (uint32_t j = 0; j < n && j < static_cast<uint32_t>(kGLen); ++j) out[j] = table_G(static_cast<int>(j));
+    return kGLen;
+  }
+  if (int e = check_bits(bits)) return e;
+  const int b = static_cast<int>(bits);
+  int len;
+  switch (which) {
+    case 1: len = (1 << b) - 1; for (int u = 0; u < len && u < static_cast<int>(n); ++u) out[u] = table_R(b, u); break;
+    case 2: len = (1 << b);     for (int c = 0; c < len && c < static_cast<int>(n); ++c) out[c] = table_L(b, c); break;
+    case 3: len = (1 << b) - 1; for (int k = 0; k < len && k < static_cast<int>(n); ++k) out[k] = table_T(b, k); break;
+    default: return STQ_EINVAL;
+  }
+  return len;
+}
+
+int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
+  if (!out || max_tensors == 0 || max_tensors > (1u << 20)) return STQ_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return STQ_EDEVICE;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return STQ_EDEVICE;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return STQ_EDEVICE;
+  std::vector<uint32_t> img;
+  if (!build_table_image(img)) return STQ_EINVAL;
+
+  stq_ctx* c = new (std::nothrow) stq_ctx();
+  if (!c) return STQ_EINVAL;
+  c->device = device;
+  c->max_tensors = max_tensors;
+  c->n_cu = static_cast<uint32_t>(prop.multiProcessorCount);
+  if (const char* e = std::getenv("STQ_GROUPS_PER_CU")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 8) c->groups_per_cu = static_cast<uint32_t>(v);
+  }
+  DeviceGuard g(device);
+  bool ok = g.ok;
+  ok = ok && hipMalloc(&c->d_tables, img.size() * 4) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_desc, sizeof(TensorDesc) * max_tensors) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_stats, sizeof(double) * kStatSlots * max_tensors) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_stats, sizeof(double) * kStatSlots * max_tensors, hipHostMallocDefault) == hipSuccess;
+  for (int k = 0; k < kRing && ok; ++k) {
+    ok = ok && hipHostMalloc(&c->h_stage[k], sizeof(TensorDesc) * max_tensors, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->stage_done[k], hipEventDisableTiming) == hipSuccess;
+  }
+  ok = ok && hipMemcpy(c->d_tables, img.data(), img.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+  ok = ok && hipMemset(c->d_stats, 0, sizeof(double) * kStatSlots * max_tensors) == hipSuccess;
+  ok = ok && hipDeviceSynchronize() == hipSuccess;
+  if (!ok) { stq_destroy(c); return STQ_EHIP; }
+  c->stat_count.assign(max_tensors, 0);
+  *out = c;
+  return STQ_OK;
+}
+
+int stq_destroy(stq_ctx* c) {
+  if (!c) return STQ_EINVAL;
+  DeviceGuard g(c->device);
+  (void)hipDeviceSynchronize();
+  if (c->d_tables) (void)hipFree(c->d_tables);
+  if (c->d_desc) (void)hipFree(c->d_desc);
+  if (c->d_stats) (void)hipFree(c->d_stats);
+  if (c->h_stats) (void)hipHostFree(c->h_stats);
+  for (int k = 0; k < kRing; ++k) {
+    if (c->h_stage[k]) (void)hipHostFree(c->h_stage[k]);
+    if (c->stage_done[k]) (void)hipEventDestroy(c->stage_done[k]);
+  }
+  delete c;
+  return STQ_OK;
+}
+
+int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+                   uint32_t block, void* stream) {
+  std::vector<TensorDesc> descs;
+  uint32_t total = 0;
+  if (int e = build_descs(ctx, tensors, n, plan, block, false, descs, &total)) return e;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  for (uint32_t l = 0; l < n; ++l) {
+    ZeroArgs a;
+    a.m_codes = descs[l].m_codes; a.m_scales = descs[l].m_scales;
+    a.v_codes = descs[l].v_codes; a.v_scales = descs[l].v_scales;
+    a.numel = descs[l].numel; a.n_tiles = descs[l].n_tiles;
+    a.bm = descs[l].bm; a.bv = descs[l].bv; a.scales_per_tile = kTile / block;
+    if (launch_zero(a, stream) != 0) return STQ_EHIP;
+  }
+  return STQ_OK;
+}
+
+int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+             const stq_hparams* hp, void* stream) {
+  if (!hp) return STQ_EINVAL;
+  if (hp->step == 0 || hp->grad_dtype > 1) return STQ_EINVAL;
+  std::vector<TensorDesc> descs;
+  uint32_t total = 0;
+  if (int e = build_descs(ctx, tensors, n, plan, hp->block, true, descs, &total)) return e;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  // refresh the device tensor table only when it differs from what is there
+  const bool same = ctx->uploaded.size() == descs.size() &&
+                    std::memcmp(ctx->uploaded.data(), descs.data(), sizeof(TensorDesc) * n) == 0;
+  if (!same) {
+    const int k = ctx->ring_pos;
+    ctx->ring_pos = (k + 1) % kRing;
+    if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
+    std::memcpy(ctx->h_stage[k], descs.data(), sizeof(TensorDesc) * n);
+    if (hipMemcpyAsync(ctx->d_desc, ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
+      return STQ_EHIP;
+    if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
+    ctx->uploaded = descs;
+  }
+
+  StepArgs a;
+  a.desc = ctx->d_desc;
+  a.n_tensors = n;
+  a.total_tiles = total;
+  a.tables = ctx->d_tables;
+  a.stats = ctx->d_stats;
+  a.beta1 = hp->beta1;
+  a.omb1 = 1.0f - hp->beta1;
+  a.beta2 = hp->beta2;
+  a.omb2 = 1.0f - hp->beta2;
+  // reciprocal bias corrections 1/(1 - beta^t): double arithmetic, one rounding to fp32
+  a.ibc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta1), static_cast<double>(hp->step))));
+  a.ibc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta2), static_cast<double>(hp->step))));
+  a.eps = hp->eps;
+  a.lr = hp->lr;
+  a.decay = 1.0f - hp->lr * hp->weight_decay;
+  a.lgK = static_cast<uint32_t>(lg_block(hp->block));
+
+  const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
+  const uint32_t max_groups = ctx->n_cu * ctx->groups_per_cu;
+  const uint32_t need_groups = (total + kWavesPerGroup - 1) / kWavesPerGroup;
+  const uint32_t groups = need_groups < max_groups ? need_groups : max_groups;
+  if (launch_step(a, hp->grad_dtype == 1, want_stats, groups, stream) != 0) return STQ_EHIP;
+  if (want_stats)
+    for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
+  return STQ_OK;
+}
+
+int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* stream) {
+  if (!ctx || !out || n == 0 || n > ctx->max_tensors) return STQ_EINVAL;
+  for (uint32_t l = 0; l < n; ++l) if (ctx->stat_count[l] == 0) return STQ_ESTATE;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bytes = sizeof(double) * kStatSlots * n;
+  if (hipMemcpyAsync(ctx->h_stats, ctx->d_stats, bytes, hipMemcpyDeviceToHost, s) != hipSuccess) return STQ_EHIP;
+  if (launch_fill_zero(reinterpret_cast<uint32_t*>(ctx->d_stats), bytes / 4, stream) != 0) return STQ_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return STQ_EHIP;
+  for (uint32_t l = 0; l < n; ++l) {
+    const double* a = ctx->h_stats + static_cast<size_t>(l) * kStatSlots;
+    stq_layer_stats& o = out[l];
+    o.count = ctx->stat_count[l];
+    o.g_sum = a[kGSum]; o.g_abs_sum = a[kGAbsSum]; o.g_sq_sum = a[kGSqSum];
+    o.m_sum = a[kMSum]; o.m_sq_sum = a[kMSqSum]; o.m_err_sq = a[kMErrSq];
+    o.v_sum = a[kVSum]; o.v_sq_sum = a[kVSqSum]; o.v_err_sq = a[kVErrSq];
+    uint32_t mx[4];
+    std::memcpy(mx, &a[kMaxGM], 16);
+    std::memcpy(&o.g_absmax, &mx[0], 4);
+    std::memcpy(&o.m_absmax, &mx[1], 4);
+    std::memcpy(&o.v_absmax, &mx[2], 4);
+    ctx->stat_count[l] = 0;
+  }
+  return STQ_OK;
+}
+
+int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state, const void* src,
+               uint32_t src_bits, void* dst, uint32_t dst_bits, void* stream) {
+  if (!ctx || !src || !dst || numel == 0 || (state != 0 && state != 1)) return STQ_EINVAL;
+  if (lg_block(block) < 0) return STQ_EBLOCK;
+  if (int e = check_bits(src_bits)) return e;
+  if (int e = check_bits(dst_bits)) return e;
+  if (!aligned(src, 256) || !aligned(dst, 256)) return STQ_EALIGN;
+  const uint64_t tiles = (numel + kTile - 1) / kTile;
+  if (tiles > 0x3FFFFFFull) return STQ_EINVAL;
+  // overlap check on the byte ranges
+  const uintptr_t s0 = reinterpret_cast<uintptr_t>(src), s1 = s0 + tiles * 256 * src_bits;
+  const uintptr_t d0 = reinterpret_cast<uintptr_t>(dst), d1 = d0 + tiles * 256 * dst_bits;
+  if (s0 < d1 && d0 < s1) return STQ_EINVAL;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  RepackArgs a;
+  a.src = static_cast<const uint32_t*>(src);
+  a.dst = static_cast<uint32_t*>(dst);
+  a.numel = numel;
+  a.n_tiles = static_cast<uint32_t>(tiles);
+  a.b_old = src_bits;
+  a.b_new = dst_bits;
+  build_repack_lut(state, static_cast<int>(src_bits), static_cast<int>(dst_bits), a.lut);
+  return launch_repack(a, stream) == 0 ? STQ_OK : STQ_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Structures shared by the host API and the gfx950 kernels of this library.
+#pragma once
+#include <cstdint>
+
+namespace stq {
+
+constexpr int kTile = 2048;         // elements per tile = 64 lanes x 32 codes
+constexpr int kWavesPerGroup = 4;   // 256-thread workgroups
+constexpr int kStatSlots = 16;      // 8-byte accumulator slots per tensor
+
+// Device-resident description of one tensor for the step kernel.
+struct TensorDesc {
+  float* param;
+  const void* grad;
+  uint32_t* m_codes;
+  float* m_scales;
+  uint32_t* v_codes;
+  float* v_scales;
+  uint64_t numel;
+  uint32_t tile_begin;  // index of this tensor's first tile in the launch-wide tile order
+  uint32_t n_tiles;
+  uint32_t bm, bv;
+};
+
+// Accumulator slots (doubles unless noted).
+enum StatSlot {
+  kGSum = 0, kGAbsSum, kGSqSum, kMSum, kMSqSum, kMErrSq, kVSum, kVSqSum, kVErrSq,
+  kMaxGM,   // two uint32: bit patterns of max|g| (low word) and max|m| (high word)
+  kMaxV     // low uint32: bit pattern of max v
+};
+
+struct StepArgs {
+  const TensorDesc* desc;
+  uint32_t n_tensors;
+  uint32_t total_tiles;
+  const uint32_t* tables;  // kTabWords words, see stq_tables.h
+  double* stats;           // [n_tensors][kStatSlots]
+  float beta1, omb1, beta2, omb2;
+  float ibc1, ibc2;        // reciprocal bias corrections 1/(1-beta^t)
+  float eps, lr, decay;    // decay = 1 - lr*weight_decay
+  uint32_t lgK;            // log2 of the block size: 6, 7 or 8
+};
+
+struct ZeroArgs {
+  uint32_t* m_codes; float* m_scales; uint32_t* v_codes; float* v_scales;
+  uint64_t numel;
+  uint32_t n_tiles, bm, bv, scales_per_tile;
+};
+
+struct RepackArgs {
+  const uint32_t* src; uint32_t* dst;
+  uint64_t numel;
+  uint32_t n_tiles, b_old, b_new;
+  uint8_t lut[256];
+};
+
+// Launchers implemented in stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
+int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream);
+int launch_zero(const ZeroArgs& a, void* stream);
+int launch_repack(const RepackArgs& a, void* stream);
+int launch_fill_zero(uint32_t* p, uint64_t words, void* stream);
+
+}  // namespace stq

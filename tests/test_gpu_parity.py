@@ -1,0 +1,261 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
+
+Bar: packed codes and block scales bit-exact; parameters within 1e-6 relative (they are in fact
+produced by the same correctly rounded fp32 operations, so equality is also asserted where it
+must hold).  Statistics are order-dependent sums: 1e-5 relative; maxima exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_06836_amd as stq
+from paper_2604_06836_amd import binding
+from workloads import configs
+from workloads.harness import DeviceModel, hparams
+
+pytestmark = pytest.mark.gpu
+
+PARAM_RTOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = stq.Context(0, 1024)
+    yield c
+    c.close()
+
+
+def oracle_states(oracle, w, plan):
+    return [oracle.State.zeros(n, w.K, bm, bv) for (_, n), (bm, bv) in zip(w.tensors, plan)]
+
+
+def assert_tensor_parity(oracle, dm, l, th_ref, st_ref, tag=""):
+    th, mw, ms, vw, vs = dm.host_state(l)
+    n, K = st_ref.numel, st_ref.K
+    assert np.array_equal(mw, oracle.pack(st_ref.um, st_ref.bm)), f"{tag} m codes tensor {l}"
+    assert np.array_equal(vw, oracle.pack(st_ref.cv, st_ref.bv)), f"{tag} v codes tensor {l}"
+    assert np.array_equal(ms.view(np.uint32), oracle.pad_scales(st_ref.sm, n, K).view(np.uint32)), f"{tag} m scales {l}"
+    assert np.array_equal(vs.view(np.uint32), oracle.pad_scales(st_ref.sv, n, K).view(np.uint32)), f"{tag} v scales {l}"
+    err = np.abs(th.astype(np.float64) - th_ref)
+    assert np.all(err <= PARAM_RTOL * np.abs(th_ref)), f"{tag} params tensor {l}: max rel {np.max(err / np.maximum(np.abs(th_ref), 1e-30))}"
+
+
+def run_both(oracle, ctx, w, plan, steps, stats_steps=(), tag=""):
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    for l in range(len(w.tensors)):  # initial state
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], tag + " init")
+    for t in range(1, steps + 1):
+        dm.set_grads(t)
+        want_stats = t in stats_steps
+        dm.step(t, stats=want_stats)
+        torch.cuda.synchronize()
+        gpu_stats = dm.ctx.stats(len(w.tensors), dm.stream) if want_stats else None
+        for l in range(len(w.tensors)):
+            s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=want_stats)
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{tag} step {t}")
+            if want_stats:
+                assert_stats_close(gpu_stats[l], s, f"{tag} step {t} tensor {l}")
+    return dm, th_ref, st_ref
+
+
+def assert_stats_close(g, o, tag):
+    assert g.count == o.count, tag
+    for name in ("g_sum", "g_abs_sum", "g_sq_sum", "m_sum", "m_sq_sum", "m_err_sq", "v_sum", "v_sq_sum", "v_err_sq"):
+        a, b = getattr(g, name), getattr(o, name)
+        # signed sums cancel: compare against the scale of the absolute sum
+        scale = {"g_sum": o.g_abs_sum, "m_sum": np.sqrt(o.m_sq_sum * o.count)}.get(name, abs(b))
+        # the kernel sums each lane's 32 elements of a tile in fp32 before widening to fp64, so
+        # terms below the smallest normal fp32 (2^-126) lose bits: absolute floor of count * 2^-126
+        assert abs(a - b) <= 1e-5 * scale + o.count * 1.2e-38, f"{tag} {name}: {a} vs {b}"
+    for name in ("g_absmax", "m_absmax", "v_absmax"):
+        assert getattr(g, name) == getattr(o, name), f"{tag} {name}"
+
+
+# ------------------------------------------------------------------ configuration 1
+def test_config1_full_size_all_steps(oracle, ctx):
+    # 768x3072 fp32 tensor, m at 8 bits, v at 4 bits, K = 128, 10 steps: every element compared
+    w = configs.get_workload("adam-1tensor")
+    run_both(oracle, ctx, w, w.initial_plan(), w.steps, stats_steps=(1, 10), tag="cfg1")
+
+
+# ------------------------------------------------- every width pair, every block size
+@pytest.mark.parametrize("K", [64, 128, 256])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_all_width_pairs(oracle, ctx, K, dtype):
+    # 49 tensors, one per (bm, bv), sizes spanning several tiles with ragged tails
+    pairs = [(bm, bv) for bm in range(2, 9) for bv in range(2, 9)]
+    rng = np.random.default_rng(K)
+    sizes = [int(rng.integers(1, 4)) * 2048 + int(rng.integers(0, 2048)) for _ in pairs]
+    w = configs.Workload(90, f"pairs-{K}-{dtype}", [(f"t{i}", n) for i, n in enumerate(sizes)], K, dtype, 3,
+                         "normal_per_tensor")
+    run_both(oracle, ctx, w, pairs, 3, stats_steps=(2,), tag=w.name)
+
+
+# ------------------------------------------------------------------------ edge cases
+@pytest.mark.parametrize("numel", [1, 3, 63, 64, 65, 2047, 2048, 2049, 4096 + 129, 10 * 2048 + 1])
+def test_ragged_sizes(oracle, ctx, numel):
+    for K in (64, 256):
+        w = configs.Workload(91, f"ragged-{numel}", [("a", numel), ("b", numel)], K, "fp32", 2, "normal")
+        run_both(oracle, ctx, w, [(5, 3), (8, 2)], 2, stats_steps=(1, 2), tag=w.name)
+
+
+def test_degenerate_values(oracle, ctx):
+    # zero gradients, one huge outlier, denormal-sized gradients, a block of equal values
+    n, K = 3 * 2048 + 700, 128
+    w = configs.Workload(92, "degenerate", [("zero", n), ("outlier", n), ("tiny", n), ("equal", n)], K, "fp32", 3, "normal")
+    plan = [(8, 4), (4, 4), (6, 5), (3, 8)]
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    for t in range(1, 4):
+        dm.set_grads(t)
+        dm.grad[0].zero_()
+        dm.grad[1][1000] = 3.0e4
+        dm.grad[1][n - 1] = -7.0e3
+        dm.grad[2].mul_(1e-17)          # g^2 ~ 1e-40: second moments below the smallest normal
+        dm.grad[3].fill_(2.5e-4)
+        dm.step(t, stats=True)
+        torch.cuda.synchronize()
+        gs = dm.ctx.stats(4, dm.stream)
+        for l in range(4):
+            s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"degenerate step {t}")
+            assert_stats_close(gs[l], s, f"degenerate step {t} tensor {l}")
+    assert np.all(st_ref[0].sm == 0) and np.all(st_ref[0].sv == 0)  # the all-zero case really was all-zero
+    assert np.all(st_ref[2].sv == 0)                                   # tiny blocks were flushed
+
+
+def test_weight_decay_and_other_hparams(oracle, ctx):
+    w = configs.Workload(93, "hp", [("a", 5000), ("b", 9000)], 128, "bf16", 4, "student_t")
+    w.hparams = dict(lr=3e-4, beta1=0.8, beta2=0.95, eps=1e-6, weight_decay=0.1)
+    run_both(oracle, ctx, w, [(6, 4), (4, 6)], 4, tag="hp")
+
+
+# -------------------------------------------------------------------------- re-pack
+@pytest.mark.parametrize("state", [0, 1])
+def test_repack_every_width_pair(oracle, ctx, state):
+    n = 2 * 2048 + 1234
+    rng = np.random.default_rng(5 + state)
+    for b_old in range(2, 9):
+        hi = 2 ** b_old - (1 if state == 0 else 0)   # linear codes never use the top value
+        codes = rng.integers(0, hi, n, dtype=np.uint8)
+        src = torch.from_numpy(oracle.pack(codes, b_old).view(np.int32)).cuda()
+        for b_new in range(2, 9):
+            cb, _ = stq.state_bytes(n, 128, b_new)
+            dst = torch.full((cb // 4,), -1, dtype=torch.int32, device="cuda")
+            ctx.repack(n, 128, state, src.data_ptr(), b_old, dst.data_ptr(), b_new,
+                       torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            want = oracle.pack(oracle.repack(codes, state, b_old, b_new), b_new)
+            assert np.array_equal(dst.cpu().numpy().view(np.uint32), want), (state, b_old, b_new)
+
+
+def test_transitions_config3_scaled(oracle, ctx):
+    # ViT-shaped tensors (reduced), Student-t gradients, K = 256, widths switching every 5 steps
+    w = configs.scaled(configs.get_workload("vit-b16"), 40_000, 12)
+    plan = w.initial_plan()
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    n_changed = 0
+    for t in range(1, 13):
+        new_plan = w.switch_plan(plan, t)
+        if new_plan != plan:
+            n_changed += dm.apply_plan(new_plan)
+            for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(plan, new_plan)):
+                if bm0 != bm1:
+                    st_ref[l].um = oracle.repack(st_ref[l].um, 0, bm0, bm1)
+                    st_ref[l].bm = bm1
+                if bv0 != bv1:
+                    st_ref[l].cv = oracle.repack(st_ref[l].cv, 1, bv0, bv1)
+                    st_ref[l].bv = bv1
+            plan = new_plan
+        dm.set_grads(t)
+        dm.step(t)
+        torch.cuda.synchronize()
+        for l in range(len(w.tensors)):
+            oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t)
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"cfg3 step {t}")
+    assert n_changed >= 2
+
+
+def test_decide_loop_config4_scaled(oracle, ctx):
+    # GPT-2-XL-shaped tensors (reduced; d = 1600 keeps the ragged blocks), bf16 gradients; every step:
+    # statistics -> decision -> re-pack -> step.  Both sides are driven by the ORACLE's plan; the plan
+    # from the GPU statistics must agree wherever the score is not within 1e-4 of a threshold.
+    w = configs.scaled(configs.get_workload("gpt2-xl"), 30_000, 14)
+    L = len(w.tensors)
+    ladder = dict(thr=(9.0, 11.0, 13.0, 15.0, 17.0), bits=(2, 3, 4, 5, 6, 8))
+    plan = [(4, 4)] * L
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    e_gpu, e_or = binding.DecideState(0, 0, 0), oracle.Ema(0, 0, 0)
+    widths_seen = set()
+    for t in range(1, 9):
+        dm.set_grads(t)
+        dm.step(t, stats=True)
+        torch.cuda.synchronize()
+        gs = dm.ctx.stats(L, dm.stream)
+        os_ = []
+        for l in range(L):
+            os_.append(oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True))
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"cfg4 step {t}")
+            assert_stats_close(gs[l], os_[l], f"cfg4 step {t} tensor {l}")
+        p_gpu, sc_gpu = stq.decide(e_gpu, gs, t, alpha=0.3, tau=4.0, v_offset=-1.0, **ladder)
+        bm, bv, sc = oracle.decide(e_or, os_, t, alpha=0.3, tau=4.0, v_offset=-1.0, **ladder)
+        new_plan = [(int(a), int(b)) for a, b in zip(bm, bv)]
+        thr = np.array(ladder["thr"])
+        for l in range(L):
+            if min(np.min(np.abs(thr - sc[l])), np.min(np.abs(thr - (sc[l] - 1.0)))) > 1e-4:
+                assert p_gpu[l] == new_plan[l]
+        widths_seen |= {b for p in new_plan for b in p}
+        dm.apply_plan(new_plan)
+        for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(plan, new_plan)):
+            if bm0 != bm1:
+                st_ref[l].um, st_ref[l].bm = oracle.repack(st_ref[l].um, 0, bm0, bm1), bm1
+            if bv0 != bv1:
+                st_ref[l].cv, st_ref[l].bv = oracle.repack(st_ref[l].cv, 1, bv0, bv1), bv1
+        plan = new_plan
+    assert len(widths_seen) >= 3
+
+
+# ------------------------------------------------- scaled copies of configs 2 and 5
+@pytest.mark.parametrize("name", ["gpt2-small", "llama7b-slice"])
+def test_scaled_configs(oracle, ctx, name):
+    w = configs.scaled(configs.get_workload(name), 50_000, 24)
+    run_both(oracle, ctx, w, w.initial_plan(), 4, stats_steps=(4,), tag=name)
+
+
+# --------------------------------------------------------------------- argument checks
+def test_argument_checks(ctx):
+    w = configs.Workload(94, "args", [("a", 4096)], 128, "fp32", 1, "normal")
+    dm = DeviceModel(ctx, w, [(8, 4)])
+    lib = stq.load_library()
+    import ctypes as C
+    hp = hparams(w, 1)
+
+    def call(tensors=dm.tensors, n=1, plan=dm.cplan, hp=hp):
+        return lib.stq_step(ctx._h, tensors, n, plan, C.byref(hp), None)
+
+    assert call(plan=binding.make_plan([(9, 4)])) == -3
+    assert call(plan=binding.make_plan([(8, 1)])) == -3
+    bad = hparams(w, 1); bad.block = 100
+    assert call(hp=bad) == -4
+    bad = hparams(w, 0)
+    assert call(hp=bad) == -1
+    assert call(n=0) == -1
+    t = binding.make_tensors([dict(param=dm.param[0].data_ptr() + 4, grad=dm.grad[0].data_ptr(), numel=4000,
+                                   m_codes=dm.m_codes[0].data_ptr(), m_scales=dm.m_scales[0].data_ptr(),
+                                   v_codes=dm.v_codes[0].data_ptr(), v_scales=dm.v_scales[0].data_ptr())])
+    assert call(tensors=t) == -2
+    t = binding.make_tensors([dict(param=None, grad=dm.grad[0].data_ptr(), numel=4000,
+                                   m_codes=dm.m_codes[0].data_ptr(), m_scales=dm.m_scales[0].data_ptr(),
+                                   v_codes=dm.v_codes[0].data_ptr(), v_scales=dm.v_scales[0].data_ptr())])
+    assert call(tensors=t) == -1
+    out = (binding.LayerStats * 1)()
+    assert lib.stq_stats(ctx._h, out, 1, None) == -7  # nothing accumulated
+    torch.cuda.synchronize()

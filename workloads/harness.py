@@ -1,0 +1,104 @@
+"""Device-memory plumbing around the C-ABI library for tests and bench.py: allocates the
+parameter, gradient and packed-state buffers of a workload as torch tensors and hands their
+addresses to the binding.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+from typing import List, Sequence, Tuple
+
+import numpy as np
+import torch
+
+import paper_2604_06836_amd as stq
+from paper_2604_06836_amd import binding
+
+from .configs import Workload
+
+
+def hparams(w: Workload, t: int, stats: bool = False) -> binding.HParams:
+    h = w.hparams
+    return binding.HParams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], t, w.K,
+                           1 if w.grad_dtype == "bf16" else 0, stq.STQ_FLAG_STATS if stats else 0)
+
+
+class DeviceModel:
+    """All tensors of one workload resident on one GPU."""
+
+    def __init__(self, ctx: stq.Context, w: Workload, plan: Sequence[Tuple[int, int]], device="cuda:0",
+                 init_params: bool = True):
+        self.ctx, self.w, self.device = ctx, w, torch.device(device)
+        self.plan = [tuple(p) for p in plan]
+        self.param: List[torch.Tensor] = []
+        self.grad: List[torch.Tensor] = []
+        self.m_codes: List[torch.Tensor] = []
+        self.v_codes: List[torch.Tensor] = []
+        self.m_scales: List[torch.Tensor] = []
+        self.v_scales: List[torch.Tensor] = []
+        gdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+        for l, (_, n) in enumerate(w.tensors):
+            bm, bv = self.plan[l]
+            self.param.append(w.gen_param(l, self.device) if init_params
+                              else torch.zeros(n, dtype=torch.float32, device=self.device))
+            self.grad.append(torch.zeros(n, dtype=gdt, device=self.device))
+            cb_m, sb = stq.state_bytes(n, w.K, bm)
+            cb_v, _ = stq.state_bytes(n, w.K, bv)
+            self.m_codes.append(torch.empty(cb_m // 4, dtype=torch.int32, device=self.device))
+            self.v_codes.append(torch.empty(cb_v // 4, dtype=torch.int32, device=self.device))
+            self.m_scales.append(torch.empty(sb // 4, dtype=torch.float32, device=self.device))
+            self.v_scales.append(torch.empty(sb // 4, dtype=torch.float32, device=self.device))
+        self._rebuild()
+        self.ctx.zero_state(self.tensors, self.cplan, w.K, self.stream)
+        torch.cuda.synchronize(self.device)
+
+    @property
+    def stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def _rebuild(self):
+        self.tensors = binding.make_tensors(
+            dict(param=p.data_ptr(), grad=g.data_ptr(), numel=p.numel(), m_codes=mc.data_ptr(),
+                 m_scales=ms.data_ptr(), v_codes=vc.data_ptr(), v_scales=vs.data_ptr())
+            for p, g, mc, ms, vc, vs in zip(self.param, self.grad, self.m_codes, self.m_scales,
+                                            self.v_codes, self.v_scales))
+        self.cplan = binding.make_plan(self.plan)
+
+    def set_grads(self, step: int):
+        for l in range(len(self.param)):
+            self.grad[l].copy_(self.w.gen_grad(l, step, self.device))
+
+    def step(self, t: int, stats: bool = False):
+        self.ctx.step(self.tensors, self.cplan, hparams(self.w, t, stats), self.stream)
+
+    def apply_plan(self, new_plan: Sequence[Tuple[int, int]]) -> int:
+        """Re-pack every state whose width changed (out of place) and adopt the new plan.
+        Returns the number of re-packed states."""
+        changed = 0
+        for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
+            n = self.param[l].numel()
+            if bm0 != bm1:
+                cb, _ = stq.state_bytes(n, self.w.K, bm1)
+                dst = torch.empty(cb // 4, dtype=torch.int32, device=self.device)
+                self.ctx.repack(n, self.w.K, 0, self.m_codes[l].data_ptr(), bm0, dst.data_ptr(), bm1, self.stream)
+                self.m_codes[l] = dst
+                changed += 1
+            if bv0 != bv1:
+                cb, _ = stq.state_bytes(n, self.w.K, bv1)
+                dst = torch.empty(cb // 4, dtype=torch.int32, device=self.device)
+                self.ctx.repack(n, self.w.K, 1, self.v_codes[l].data_ptr(), bv0, dst.data_ptr(), bv1, self.stream)
+                self.v_codes[l] = dst
+                changed += 1
+        self.plan = [tuple(p) for p in new_plan]
+        self._rebuild()
+        return changed
+
+    # ----------------------------------------------------------- host copies
+    def host_state(self, l: int):
+        """(param, m_code_words, m_scales, v_code_words, v_scales) of tensor l as numpy arrays."""
+        return (self.param[l].cpu().numpy(),
+                self.m_codes[l].cpu().numpy().view(np.uint32), self.m_scales[l].cpu().numpy(),
+                self.v_codes[l].cpu().numpy().view(np.uint32), self.v_scales[l].cpu().numpy())
+
+    def host_grad(self, l: int) -> np.ndarray:
+        g = self.grad[l]
+        if g.dtype == torch.bfloat16:
+            return g.view(torch.int16).cpu().numpy().view(np.uint16)
+        return g.cpu().numpy()
