@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized Adam step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A "step" is one pass of the whole hot path over every tensor of the workload: the fused
+dequant -> Adam -> requant kernel (plus, for the workloads that have them, statistics read-back,
+the bit-width decision and the re-pack of changed states).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line: params/s, the roofline of the dominant kernel from HIP-event
+durations measured around every launch, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2):
+    """The oracle as it stands, one thread, on the first `budget_elems` parameters of the workload."""
+    import numpy as np
+    import torch
+    from oracle import stq_oracle as oracle
+    oracle.lib()
+    sample, acc = [], 0
+    for l, (_, n) in enumerate(w.tensors):
+        take = min(n, budget_elems - acc)
+        if take <= 0:
+            break
+        sample.append((l, take))
+        acc += take
+    data = []
+    for l, n in sample:
+        th = w.gen_param(l)[:n].numpy().copy()
+        g = w.gen_grad(l, 1)[:n]
+        g = g.view(torch.int16).numpy().view(np.uint16).copy() if w.grad_dtype == "bf16" else g.numpy().copy()
+        data.append((th, g, oracle.State.zeros(n, w.K, *plan[l])))
+    t0 = time.perf_counter()
+    for t in range(1, steps + 1):
+        for th, g, st in data:
+            oracle.step(th, g, st, **w.hparams, t=t)
+    dt = time.perf_counter() - t0
+    return {"value": acc * steps / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d parameters of the workload (%d tensors), %d steps, %.1f s" % (acc, len(sample), steps, dt)}
+
+
+def calibrate_ladder(scores, probs):
+    """Thresholds at the score quantiles that give the widths the target frequencies."""
+    import numpy as np
+    cum = np.cumsum(probs)[:-1]
+    return tuple(float(x) for x in np.quantile(np.asarray(scores)[np.isfinite(scores)], cum))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt2-small")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2604_06836_amd as stq
+    from paper_2604_06836_amd import binding
+    from workloads import configs
+    from workloads.harness import DeviceModel, hparams
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (and libstq.so built for gfx950)")
+    stq.load_library()  # fails loudly if the HIP library is missing
+    w = configs.get_workload(args.workload)
+    steps = args.steps if args.steps is not None else w.steps
+    L = len(w.tensors)
+    plan = w.initial_plan()
+    ctx = stq.Context(0, max(L, 16))
+    dm = DeviceModel(ctx, w, plan)
+    stream = torch.cuda.current_stream()
+
+    # two resident gradient sets, alternated, so consecutive steps see different gradients
+    grads = [dm.grad, [torch.empty_like(g) for g in dm.grad]]
+    for k in (0, 1):
+        for l in range(L):
+            grads[k][l].copy_(w.gen_grad(l, k + 1, dm.device))
+    tensor_sets = []
+    for k in (0, 1):
+        dm.grad = grads[k]
+        dm._rebuild()
+        tensor_sets.append(dm.tensors)
+
+    decide_every_step = w.transitions == "decide_every_step"
+    ema = binding.DecideState(0, 0, 0)
+    ladder = None
+    kernel_ms, repacked = [], 0
+
+    def one_step(t, timed):
+        nonlocal plan, ladder, repacked
+        k = t % 2
+        dm.grad = grads[k]
+        if w.transitions == "switch10pct_every5":
+            new_plan = w.switch_plan(plan, t)
+            if new_plan != plan:
+                repacked += dm.apply_plan(new_plan)
+                plan = new_plan
+                for kk in (0, 1):
+                    dm.grad = grads[kk]; dm._rebuild(); tensor_sets[kk] = dm.tensors
+                dm.grad = grads[k]
+        dm.tensors = tensor_sets[k]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        dm.step(t, stats=decide_every_step)
+        e1.record(stream)
+        if timed:
+            kernel_ms.append((e0, e1))
+        if decide_every_step:
+            st = ctx.stats(L, dm.stream)
+            if ladder is None:
+                _, sc = stq.decide(binding.DecideState(0, 0, 0), st, t, alpha=0.3, tau=4.0, thr=(), bits=(4,))
+                ladder = calibrate_ladder(sc, w.p_m)
+            new_plan, _ = stq.decide(ema, st, t, alpha=0.3, tau=4.0, v_offset=-0.5, thr=ladder, bits=w.bits_m)
+            repacked += dm.apply_plan(new_plan)
+            plan = new_plan
+            for kk in (0, 1):
+                dm.grad = grads[kk]; dm._rebuild(); tensor_sets[kk] = dm.tensors
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        one_step(t, False)
+    torch.cuda.synchronize()
+    repacked = 0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        t += 1
+        one_step(t, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    n = w.numel
+    ms_per_step = dt * 1e3 / steps
+    kms = [a.elapsed_time(b) for a, b in kernel_ms]
+    k_avg_ms = sum(kms) / len(kms)
+    bpp = w.bytes_per_param(plan)
+    alg_bytes = bpp * n
+    achieved = alg_bytes / (k_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "quantized-Adam step params/sec",
+        "value": n * steps / dt,
+        "unit": "params/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "configs_index": w.cfg, "params": n, "tensors": L, "block": w.K,
+                   "grad_dtype": w.grad_dtype, "avg_state_bits": round(w.avg_bits(plan), 3),
+                   "repacked_states_in_timed_region": repacked},
+        "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms_avg": k_avg_ms, "algorithmic_bytes_per_param": bpp,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        tr = json.load(open(traffic_file)).get(w.name)
+        if tr:
+            out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, w.initial_plan())
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

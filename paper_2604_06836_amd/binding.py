@@ -11,7 +11,7 @@ import os
 from typing import Iterable, Optional, Sequence
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libstq.so")
+_LIB_PATH = os.environ.get("STQ_LIBRARY", os.path.join(_PKG, "libstq.so"))  # override: another build of the same ABI
 
 STQ_FLAG_STATS = 1
 STQ_DECIDE_R_ALG1 = 1

@@ -5,7 +5,7 @@
 namespace stq {
 
 constexpr int kTile = 2048;         // elements per tile = 64 lanes x 32 codes
-constexpr int kWavesPerGroup = 4;   // 256-thread workgroups
+constexpr int kWavesPerGroup = 8;   // 512-thread workgroups
 constexpr int kStatSlots = 16;      // 8-byte accumulator slots per tensor
 
 // Device-resident description of one tensor for the step kernel.
@@ -54,7 +54,7 @@ struct RepackArgs {
   uint8_t lut[256];
 };
 
-// Launchers implemented in stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
+// Launchers implemented in stq_step.hip and stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
 int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream);
 int launch_zero(const ZeroArgs& a, void* stream);
 int launch_repack(const RepackArgs& a, void* stream);

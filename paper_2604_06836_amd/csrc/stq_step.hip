@@ -1,0 +1,603 @@
+// gfx950 kernel of the quantized Adam step: the per-layer loop body of Algorithm 1 of the paper
+// (moment update, Quantize(m,'linear'), Quantize(v,'log'), bias correction of the quantized
+// moments, decoupled-weight-decay update) with the block quantizers of Section 3.5 and the
+// per-layer statistics of Section 3.3, fused into one pass over HBM.
+//
+// Arithmetic contract: IEEE binary32, every operation rounded on its own (build with
+// -ffp-contract=off); division and square root are the correctly rounded ones.
+//
+// Work decomposition: one wavefront owns one 2048-element tile at a time and processes it as two
+// halves of 4 rows.  In row i lane j holds the 4 elements 256*i + 4*j + e, so every parameter and
+// gradient access is a coalesced 16-byte (8-byte for bf16) per-lane access, and a block of
+// K = 64/128/256 consecutive elements is 16/32/64 neighbouring lanes of one row.  The lane's 32
+// codes of a state are exactly b 32-bit words; word p of all lanes is one contiguous 256-byte row
+// of the code buffer.  A half uses the words that hold its 16 codes (the middle word of an odd
+// width is written by the second half, the first half hands its 16 bits over in a register).
+//
+// Only the bit-stream unpack and pack are specialised per width (small switch arms); all
+// arithmetic is width-generic and takes the width through table offsets and constants.
+#include <hip/hip_runtime.h>
+
+#include <cfloat>
+#include <cstdint>
+
+#include "stq_device.h"
+#include "stq_tables.h"
+
+#pragma clang fp contract(off)
+
+namespace stq {
+namespace {
+
+constexpr int XS = 68;  // row stride (words) of the transpose scratch: keeps 16-byte alignment, shifts banks
+// per-wave LDS scratch: XR[8][XS] partial maxima (later the den table), old scales, new scales, reciprocals
+constexpr int kWaveScratch = 8 * XS + 3 * 64;
+constexpr int kLdsWords = kTabWords + kWavesPerGroup * kWaveScratch;
+constexpr int kStatFlushTiles = 16;  // fp32 lane sums are widened to fp64 every this many tiles
+constexpr uint32_t kDenEntries = 256;  // capacity of the per-wave den table (8 bytes per entry, inside XR)
+
+// Pointers that arrive through the tensor table are loaded from memory, so the compiler cannot
+// see that they are global; say so, to get global_load/global_store instead of flat accesses.
+#define STQ_GLOBAL __attribute__((address_space(1)))
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <class T>
+__device__ __forceinline__ STQ_GLOBAL T* as_global(T* p) { return (STQ_GLOBAL T*)p; }
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// value at byte offset `off` of an LDS float table
+__device__ __forceinline__ float lds_at(const float* base, uint32_t off) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + off);
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+  // LDS operations of one wavefront execute in order; this only stops the compiler from moving
+  // accesses of other lanes' data across the point.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---------------------------------------------------------------- bit streams
+// Within a half, code n (0..15) of width B sits at bits [n*B, n*B+B) of the half's local stream.
+template <int B>
+__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[5], int n) {
+  const int off = n * B, p = off >> 5, sh = off & 31;
+  constexpr uint32_t mask = (1u << B) - 1u;
+  if (sh + B <= 32) return (w[p] >> sh) & mask;
+  return ((w[p] >> sh) | (w[p + 1] << (32 - sh))) & mask;
+}
+
+template <int B>
+__device__ __forceinline__ void insert(uint32_t (&w)[5], int n, uint32_t code) {
+  const int off = n * B, p = off >> 5, sh = off & 31;
+  if (sh == 0) w[p] = code; else w[p] |= code << sh;
+  if (sh + B > 32) w[p + 1] = code >> (32 - sh);  // first bits of the next word
+}
+
+// The 16 codes of half h as byte offsets into the width's value table: (code << 2) | (4 << B).
+// lw holds the words (h*B)>>1 .. of the lane's B words; for an odd width the second half starts
+// 16 bits into its first word.
+template <int B>
+__device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[4], uint32_t h, uint32_t (&off)[16]) {
+  constexpr int NW = (B + 1) / 2;
+  uint32_t w[5];
+  if (B & 1) {
+    const uint32_t s0 = h * 16u;
+#pragma unroll
+    for (int k = 0; k < NW; ++k)
+      w[k] = __builtin_amdgcn_alignbit(k + 1 < NW ? lw[k + 1] : 0u, lw[k], s0);
+  } else {
+#pragma unroll
+    for (int k = 0; k < NW; ++k) w[k] = lw[k];
+  }
+  w[NW] = 0u;
+#pragma unroll
+  for (int n = 0; n < 16; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
+}
+
+// Pack the 16 codes of half h and store its words.  `carry` holds, in its upper 16 bits, the 16
+// bits the first half of an odd width leaves for the word both halves share.
+template <int B>
+__device__ __forceinline__ void pack_store(const uint32_t (&code)[16], STQ_GLOBAL uint32_t* C, uint32_t h,
+                                           uint32_t& carry, int lane) {
+  constexpr int NW = (B + 1) / 2;
+  uint32_t ow[5];
+#pragma unroll
+  for (int n = 0; n < 16; ++n) insert<B>(ow, n, code[n]);
+  if (B & 1) {
+    if (h == 0) {
+#pragma unroll
+      for (int k = 0; k < NW - 1; ++k) C[k * 64 + lane] = ow[k];
+      carry = ow[NW - 1] << 16;
+    } else {
+      STQ_GLOBAL uint32_t* C1 = C + (B / 2) * 64;
+#pragma unroll
+      for (int k = 0; k < NW; ++k)
+        C1[k * 64 + lane] = __builtin_amdgcn_alignbit(ow[k], k == 0 ? carry : ow[k - 1], 16);
+    }
+  } else {
+    STQ_GLOBAL uint32_t* C1 = C + h * (B / 2) * 64;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) C1[k * 64 + lane] = ow[k];
+  }
+}
+
+#define STQ_SWITCH_BITS(bits, CALL)               \
+  switch (bits) {                                 \
+    case 2: { constexpr int B = 2; CALL; } break; \
+    case 3: { constexpr int B = 3; CALL; } break; \
+    case 4: { constexpr int B = 4; CALL; } break; \
+    case 5: { constexpr int B = 5; CALL; } break; \
+    case 6: { constexpr int B = 6; CALL; } break; \
+    case 7: { constexpr int B = 7; CALL; } break; \
+    default: { constexpr int B = 8; CALL; } break; \
+  }
+
+// element n (0..15) of this lane in half h is real (not pad) in a tile with n_valid elements
+__device__ __forceinline__ bool is_valid(int n, uint32_t h, int lane, uint32_t n_valid) {
+  return (1024u * h + static_cast<uint32_t>(256 * (n >> 2) + 4 * lane + (n & 3))) < n_valid;
+}
+
+// -------------------------------------------------------------------- statistics
+struct LaneStats {
+  // fp32 running sums of this lane since the last widening, and running maxima since the last flush
+  float g_sum, g_abs, g_sq, m_sum, m_sq, m_err, v_sum, v_sq, v_err;
+  float g_max, m_max, v_max;
+  double wide;  // lane k < 9 holds the fp64 total of sum k for the current tensor
+  uint32_t tiles;
+  __device__ __forceinline__ void clear_sums() {
+    g_sum = g_abs = g_sq = m_sum = m_sq = m_err = v_sum = v_sq = v_err = 0.0f;
+    tiles = 0;
+  }
+  __device__ __forceinline__ void clear_all() {
+    clear_sums();
+    g_max = m_max = v_max = 0.0f;
+    wide = 0.0;
+  }
+};
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+
+// fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
+__device__ __forceinline__ void widen_stats(LaneStats& s, int lane) {
+  const float v[9] = {s.g_sum, s.g_abs, s.g_sq, s.m_sum, s.m_sq, s.m_err, s.v_sum, s.v_sq, s.v_err};
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    const double t = wave_sum(static_cast<double>(v[k]));
+    if (lane == k) s.wide += t;
+  }
+  s.clear_sums();
+}
+
+__device__ __forceinline__ void flush_stats(LaneStats& s, double* slot, int lane) {
+  widen_stats(s, lane);
+  const float gm = wave_max(s.g_max), mm = wave_max(s.m_max), vm = wave_max(s.v_max);
+  if (lane < 9) atomicAdd(&slot[lane], s.wide);
+  if (lane == 0) {
+    // non-negative floats order like their bit patterns
+    uint32_t* mx = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);
+    atomicMax(&mx[0], f2u(gm));
+    atomicMax(&mx[1], f2u(mm));
+    atomicMax(&mx[2], f2u(vm));
+  }
+  s.clear_all();
+}
+
+// ------------------------------------------------------------------ update
+struct UpdateArgs {
+  float ibc1, ibc2, eps, lr, decay;
+};
+
+// theta' = theta*decay - lr * (mt / den), with the quotient computed either by the correctly
+// rounded division, or (FAST) from the correctly rounded reciprocal rden = 1/den by two
+// residual corrections, which gives the same correctly rounded quotient when no intermediate
+// underflows or overflows (the caller checks the ranges that guarantee it).
+template <bool FAST>
+__device__ __forceinline__ float updated_param(float theta, float mt, float den, float rden, const UpdateArgs& u) {
+  float ratio;
+  if (FAST) {
+    const float q0 = mt * rden;
+    const float r0 = __builtin_fmaf(-den, q0, mt);
+    const float q1 = __builtin_fmaf(r0, rden, q0);
+    const float r1 = __builtin_fmaf(-den, q1, mt);
+    ratio = __builtin_fmaf(r1, rden, q1);
+  } else {
+    ratio = mt / den;
+  }
+  const float upd = u.lr * ratio;
+  const float dec = theta * u.decay;
+  return dec - upd;
+}
+
+// Logarithmic quantization of v fused with the parameter update, for any width.  The code is the
+// number of thresholds at or below rho = v/blockmax, found with one bucket lookup and one compare
+// on the bit pattern of rho.  The update needs den = sqrt(vq*ibc2) + eps of the quantized value
+// vq, which takes only 2^b values per block: with TABLE they (and their reciprocals) are read from
+// the per-wave table DEN, indexed by (row, block, code); otherwise they are computed per element.
+// mq holds the quantized first moments; theta is replaced by the new parameters.
+template <bool STATS, bool TAIL, bool TABLE, bool FAST>
+__device__ __forceinline__ void quant2_update(const float (&v)[16], const float (&mq)[16], float (&theta)[16],
+                                              uint32_t (&code)[16], const float (&sn)[4], const float (&inv)[4],
+                                              const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
+                                              const uint32_t (&den_row)[4], const UpdateArgs& u, uint32_t h, int lane,
+                                              uint32_t n_valid, LaneStats& st) {
+#pragma unroll
+  for (int n = 0; n < 16; ++n) {
+    const int i = n >> 2;
+    const float rho = v[n] * inv[i];
+    const uint32_t bits = f2u(rho);
+    const uint32_t idx = min(kVqTop - (bits >> kVqShift), static_cast<uint32_t>(kVqBuckets - 1));
+    const uint2 e = VQ[idx];
+    uint32_t c = e.y + (bits >= e.x ? 1u : 0u);
+    if (TAIL && !is_valid(n, h, lane, n_valid)) c = 0;
+    code[n] = c;
+    if (STATS) {
+      float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
+      if (TAIL && !is_valid(n, h, lane, n_valid)) vq = 0.0f;
+      const float d = v[n] - vq;
+      st.v_sum += v[n];
+      st.v_sq += v[n] * v[n];
+      st.v_err += d * d;
+    }
+    const float mt = mq[n] * u.ibc1;
+    if (TABLE) {
+      const float2 dr = DEN[den_row[i] + c];
+      theta[n] = updated_param<FAST>(theta[n], mt, dr.x, dr.y, u);
+    } else {
+      const float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
+      const float vt = vq * u.ibc2;
+      const float den = __builtin_sqrtf(vt) + u.eps;
+      theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, u);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ one half tile
+// Lane L = (value vL = L&7, lane group qL = L>>3) owns one (state, row) pair's block scale:
+// state = vL>>2, row = 4h + (vL&3), block within the row = qL >> (lgK-5).
+template <bool BF16, bool STATS, bool TAIL>
+__device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile, uint32_t h, uint32_t n_valid,
+                                             const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
+                                             uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
+  // Everything derived from the lane index and the block size is cheap to recompute.  Hide the two
+  // from loop-invariant code motion, which would otherwise keep dozens of such values live across
+  // the whole tile loop and spill them.
+  asm volatile("" : "+v"(lane));
+  uint32_t lgK = a.lgK;
+  asm volatile("" : "+s"(lgK));
+  const uint32_t bm = d.bm, bv = d.bv;
+  const size_t e0 = static_cast<size_t>(tile) * kTile + 1024u * h;
+  STQ_GLOBAL float* P = as_global(d.param + e0);
+  STQ_GLOBAL uint32_t* CM = as_global(d.m_codes + static_cast<size_t>(tile) * 64u * bm);
+  STQ_GLOBAL uint32_t* CV = as_global(d.v_codes + static_cast<size_t>(tile) * 64u * bv);
+  const size_t sbase = static_cast<size_t>(tile) << (11 - lgK);  // scales per tile = 2048/K
+  const int vL = lane & 7, qL = lane >> 3;
+  const uint32_t sidx = ((4u * h + static_cast<uint32_t>(vL & 3)) << (8 - lgK)) + (static_cast<uint32_t>(qL) >> (lgK - 5));
+  STQ_GLOBAL float* SC = as_global((vL >> 2) ? d.v_scales : d.m_scales);
+
+  // ---- loads for the moment phase --------------------------------------------
+  const float sc_old = SC[sbase + sidx];
+  uint32_t lwm[4], lwv[4];  // the code words of this half: words (h*b)>>1 .. of the lane's b words
+  {
+    const uint32_t nwm = (bm + 1) >> 1, nwv = (bv + 1) >> 1;
+    STQ_GLOBAL const uint32_t* cm = CM + ((h * bm) >> 1) * 64 + lane;
+    STQ_GLOBAL const uint32_t* cv = CV + ((h * bv) >> 1) * 64 + lane;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? cm[k * 64] : 0u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? cv[k * 64] : 0u;
+  }
+  float g[16];
+  {
+    STQ_GLOBAL const float* G32 = as_global(static_cast<const float*>(d.grad) + e0);
+    STQ_GLOBAL const uint16_t* G16 = as_global(static_cast<const uint16_t*>(d.grad) + e0);
+    if (!TAIL) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (BF16) {
+          const u32x2 r = reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[lane];
+          g[4 * i + 0] = u2f(r.x << 16); g[4 * i + 1] = u2f(r.x & 0xFFFF0000u);
+          g[4 * i + 2] = u2f(r.y << 16); g[4 * i + 3] = u2f(r.y & 0xFFFF0000u);
+        } else {
+          const f32x4 r = reinterpret_cast<STQ_GLOBAL const f32x4*>(G32 + 256 * i)[lane];
+          g[4 * i + 0] = r.x; g[4 * i + 1] = r.y; g[4 * i + 2] = r.z; g[4 * i + 3] = r.w;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < 16; ++n) {
+        float x = 0.0f;
+        if (is_valid(n, h, lane, n_valid)) {
+          const int idx = 256 * (n >> 2) + 4 * lane + (n & 3);
+          x = BF16 ? u2f(static_cast<uint32_t>(G16[idx]) << 16) : G32[idx];
+        }
+        g[n] = x;
+      }
+    }
+  }
+
+  // old scales to every lane that needs them: lane j reads the 8 values of its lane group
+  float* wsf = reinterpret_cast<float*>(ws);
+  float* XR = wsf;                // [8][XS]
+  float* SO = wsf + 8 * XS;       // [64] old scales by owner lane
+  float* SN = SO + 64;            // [64] new scales
+  float* SI = SN + 64;            // [64] reciprocals of the new scales
+  SO[lane] = sc_old;
+  wave_lds_sync();
+  float som[4], sov[4];
+  {
+    const float4* s4 = reinterpret_cast<const float4*>(SO + (lane >> 3) * 8);
+    const float4 a0 = s4[0], a1 = s4[1];
+    som[0] = a0.x; som[1] = a0.y; som[2] = a0.z; som[3] = a0.w;
+    sov[0] = a1.x; sov[1] = a1.y; sov[2] = a1.z; sov[3] = a1.w;
+  }
+
+  if (STATS) {
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      st.g_sum += g[n];
+      st.g_abs += fabsf(g[n]);
+      st.g_sq += g[n] * g[n];
+      st.g_max = fmaxf(st.g_max, fabsf(g[n]));
+    }
+  }
+
+  // ---- moments: m_t = beta1*m_{t-1} + (1-beta1)*g ; v_t = beta2*v_{t-1} + (1-beta2)*g^2 ----
+  const float* Rreg = reinterpret_cast<const float*>(lds) + kTabROff;  // value tables, see stq_tables.h
+  const float* Lreg = reinterpret_cast<const float*>(lds) + kTabLOff;
+  float m[16], v[16];
+  {
+    uint32_t off[16];
+    STQ_SWITCH_BITS(bm, (unpack_offsets<B>(lwm, h, off)));
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const float mh = som[n >> 2] * lds_at(Rreg, off[n]);
+      const float x = a.beta1 * mh, y = a.omb1 * g[n];
+      m[n] = x + y;
+    }
+    STQ_SWITCH_BITS(bv, (unpack_offsets<B>(lwv, h, off)));
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const float vh = sov[n >> 2] * lds_at(Lreg, off[n]);
+      const float gg = g[n] * g[n];
+      const float x = a.beta2 * vh, y = a.omb2 * gg;
+      v[n] = x + y;
+    }
+  }
+  if (TAIL) {
+#pragma unroll
+    for (int n = 0; n < 16; ++n)
+      if (!is_valid(n, h, lane, n_valid)) { m[n] = 0.0f; v[n] = 0.0f; }
+  }
+
+  // ---- parameters: issued here so that they arrive while the block maxima are reduced ----
+  float theta[16];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (!TAIL) {
+      const f32x4 t = reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[lane];
+      theta[4 * i] = t.x; theta[4 * i + 1] = t.y; theta[4 * i + 2] = t.z; theta[4 * i + 3] = t.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        theta[4 * i + e] = is_valid(4 * i + e, h, lane, n_valid) ? P[256 * i + 4 * lane + e] : 0.0f;
+    }
+  }
+
+  // ---- block maxima: lane partials -> LDS transpose -> one owner lane per (state,row,block)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float pm = fmaxf(fmaxf(fabsf(m[4 * i]), fabsf(m[4 * i + 1])), fmaxf(fabsf(m[4 * i + 2]), fabsf(m[4 * i + 3])));
+    const float pv = fmaxf(fmaxf(v[4 * i], v[4 * i + 1]), fmaxf(v[4 * i + 2], v[4 * i + 3]));
+    XR[i * XS + lane] = pm;
+    XR[(4 + i) * XS + lane] = pv;
+  }
+  wave_lds_sync();
+  float r;
+  {
+    const float4* x4 = reinterpret_cast<const float4*>(XR + vL * XS + qL * 8);
+    const float4 t0 = x4[0], t1 = x4[1];
+    r = fmaxf(fmaxf(fmaxf(t0.x, t0.y), fmaxf(t0.z, t0.w)), fmaxf(fmaxf(t1.x, t1.y), fmaxf(t1.z, t1.w)));
+  }
+  r = fmaxf(r, __shfl_xor(r, 8, 64));
+  if (lgK >= 7) r = fmaxf(r, __shfl_xor(r, 16, 64));
+  if (lgK == 8) r = fmaxf(r, __shfl_xor(r, 32, 64));
+  if (STATS) {
+    if (vL < 4) st.m_max = fmaxf(st.m_max, r); else st.v_max = fmaxf(st.v_max, r);
+  }
+  // a block whose maximum is below the smallest normal number is stored as all-zero
+  const float sc_new = (r < FLT_MIN) ? 0.0f : r;
+  const float sc_inv = (sc_new > 0.0f) ? 1.0f / sc_new : 0.0f;
+  SN[lane] = sc_new;
+  SI[lane] = sc_inv;
+  if ((static_cast<uint32_t>(qL) & ((1u << (lgK - 5)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
+  wave_lds_sync();
+
+  // ---- table of den = sqrt(vq*ibc2) + eps and 1/den per (row, block, second-moment code) ----
+  // Used when a level serves at least four elements: entries = (1024/K) << bv <= 256.  The table
+  // takes the place of XR, whose last readers have finished.
+  const UpdateArgs ua = {a.ibc1, a.ibc2, a.eps, a.lr, a.decay};
+  const uint32_t n_entries = (1024u >> lgK) << bv;
+  const bool use_table = n_entries <= kDenEntries;
+  const uint32_t l_base = 4u << bv;
+  float2* DEN = reinterpret_cast<float2*>(XR);
+  bool fast_div = false;
+  if (use_table) {
+    // the fast quotient needs every operand in a range where no residual underflows or overflows
+    bool bad = false;
+    if (vL < 4) {
+      const float x = sc_new * a.ibc1;
+      bad = !(sc_new == 0.0f || (x >= 0x1p-40f && x <= 0x1p40f));
+    }
+    for (uint32_t e = lane; e < n_entries; e += 64) {
+      const uint32_t c = e & ((1u << bv) - 1u), rg = e >> bv;
+      const uint32_t row = rg >> (8 - lgK), blk = rg & ((1u << (8 - lgK)) - 1u);
+      const float sv = SN[((blk << (lgK - 5)) << 3) + 4 + row];
+      const float vq = sv * lds_at(Lreg, (c << 2) | l_base);
+      const float vt = vq * a.ibc2;
+      const float den = __builtin_sqrtf(vt) + a.eps;
+      const float rden = 1.0f / den;
+      bad = bad || !(den >= 0x1p-40f && den <= 0x1p40f) || (f2u(den) & 0x7FFFFFu) == 0x7FFFFFu;
+      DEN[e] = make_float2(den, rden);
+    }
+    fast_div = !__any(bad);
+    wave_lds_sync();
+  }
+
+  // ---- linear symmetric quantization of m; m is replaced by its quantized value ----
+  {
+    float sn[4], inv[4];
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(SN + (lane >> 3) * 8);
+      const float4 b0 = *reinterpret_cast<const float4*>(SI + (lane >> 3) * 8);
+      sn[0] = a0.x; sn[1] = a0.y; sn[2] = a0.z; sn[3] = a0.w;
+      inv[0] = b0.x; inv[1] = b0.y; inv[2] = b0.z; inv[3] = b0.w;
+    }
+    const int qmax = (1 << (bm - 1)) - 1;
+    const float qmaxf = static_cast<float>(qmax);
+    const uint32_t r_base = 4u << bm;
+    uint32_t code[16];
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const int i = n >> 2;
+      const float t = (m[n] * inv[i]) * qmaxf;
+      // round half to even: adding 1.5*2^23 leaves the integer in the low mantissa bits (|t| <= 127.5)
+      const float rr = t + 12582912.0f;
+      int q = static_cast<int>(f2u(rr)) - (0x4B400000 - qmax);
+      q = min(max(q, 0), 2 * qmax);
+      uint32_t u = static_cast<uint32_t>(q);
+      if (TAIL && !is_valid(n, h, lane, n_valid)) u = 0;
+      code[n] = u;
+      float mq = sn[i] * lds_at(Rreg, (u << 2) | r_base);
+      if (STATS) {
+        if (TAIL && !is_valid(n, h, lane, n_valid)) mq = 0.0f;
+        const float dd = m[n] - mq;
+        st.m_sum += m[n];
+        st.m_sq += m[n] * m[n];
+        st.m_err += dd * dd;
+      }
+      m[n] = mq;
+    }
+    STQ_SWITCH_BITS(bm, (pack_store<B>(code, CM, h, carry_m, lane)));
+  }
+
+  // ---- logarithmic quantization of v and the parameter update ----
+  {
+    float sn[4], inv[4];
+    {
+      const float4 a1 = *reinterpret_cast<const float4*>(SN + (lane >> 3) * 8 + 4);
+      const float4 b1 = *reinterpret_cast<const float4*>(SI + (lane >> 3) * 8 + 4);
+      sn[0] = a1.x; sn[1] = a1.y; sn[2] = a1.z; sn[3] = a1.w;
+      inv[0] = b1.x; inv[1] = b1.y; inv[2] = b1.z; inv[3] = b1.w;
+    }
+    const uint2* VQ = reinterpret_cast<const uint2*>(lds + kTabVqOff) + (bv - 2) * kVqBuckets;
+    // den table entry ((row*G + block) << bv) + c, G = 256/K blocks per row
+    uint32_t den_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bv);
+    uint32_t code[16];
+    if (use_table) {
+      if (fast_div)
+        quant2_update<STATS, TAIL, true, true>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+      else
+        quant2_update<STATS, TAIL, true, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+    } else {
+      quant2_update<STATS, TAIL, false, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+    }
+    STQ_SWITCH_BITS(bv, (pack_store<B>(code, CV, h, carry_v, lane)));
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (!TAIL) {
+      reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[lane] =
+          f32x4{theta[4 * i], theta[4 * i + 1], theta[4 * i + 2], theta[4 * i + 3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (is_valid(4 * i + e, h, lane, n_valid)) P[256 * i + 4 * lane + e] = theta[4 * i + e];
+    }
+  }
+}
+
+// -------------------------------------------------------------- step kernel
+// Every wavefront takes a contiguous range of the launch-wide tile order, so it crosses few
+// tensor boundaries and flushes its statistics once per tensor it touched.
+template <bool BF16, bool STATS>
+__global__ __launch_bounds__(64 * kWavesPerGroup, 4) void step_kernel(const StepArgs a) {
+  __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
+  for (int i = threadIdx.x; i < kTabWords; i += 64 * kWavesPerGroup) lds[i] = a.tables[i];
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t* ws = lds + kTabWords + wave * kWaveScratch;
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * kWavesPerGroup;
+  const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * kWavesPerGroup + wave;
+  uint32_t t = static_cast<uint32_t>(a.total_tiles * gw / n_waves);
+  const uint32_t t_end = static_cast<uint32_t>(a.total_tiles * (gw + 1) / n_waves);
+  if (t >= t_end) return;
+
+  // tensor holding tile t: last l with tile_begin <= t
+  uint32_t lo = 0, hi = a.n_tensors - 1;
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi + 1) >> 1;
+    if (a.desc[mid].tile_begin <= t) lo = mid; else hi = mid - 1;
+  }
+  uint32_t l = __builtin_amdgcn_readfirstlane(lo);
+
+  LaneStats st;
+  if (STATS) st.clear_all();
+  while (t < t_end) {
+    const TensorDesc d = a.desc[l];
+    const uint32_t stop = min(t_end, d.tile_begin + d.n_tiles);
+    for (; t < stop; ++t) {
+      const uint32_t tile = t - d.tile_begin;
+      const uint64_t left = d.numel - static_cast<uint64_t>(tile) * kTile;
+      uint32_t carry_m = 0, carry_v = 0;
+      if (left >= static_cast<uint64_t>(kTile)) {
+#pragma nounroll
+        for (uint32_t h = 0; h < 2; ++h)
+          process_half<BF16, STATS, false>(d, tile, h, kTile, a, lds, ws, lane, carry_m, carry_v, st);
+      } else {
+#pragma nounroll
+        for (uint32_t h = 0; h < 2; ++h)
+          process_half<BF16, STATS, true>(d, tile, h, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
+                                          carry_v, st);
+      }
+      if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
+    }
+    if (STATS) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+    ++l;
+  }
+}
+
+}  // namespace
+
+int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(groups), block(64 * kWavesPerGroup);
+  if (grad_bf16) {
+    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<true, false>), grid, block, 0, s, a);
+  } else {
+    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<false, false>), grid, block, 0, s, a);
+  }
+  return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace stq

@@ -26,8 +26,8 @@ bool build_table_image(std::vector<uint32_t>& img) {
   img.assign(kTabWords, 0u);
   for (int b = kMinBits; b <= kMaxBits; ++b) {
     const int qmax = (1 << (b - 1)) - 1, kmax = (1 << b) - 1;
-    for (int u = 0; u <= 2 * qmax; ++u) img[kTabROff + (1 << b) - 4 + u] = f2u(table_R(b, u));
-    for (int c = 0; c <= kmax; ++c) img[kTabLOff + (1 << b) - 4 + c] = f2u(table_L(b, c));
+    for (int u = 0; u <= 2 * qmax; ++u) img[kTabROff + (1 << b) + u] = f2u(table_R(b, u));
+    for (int c = 0; c <= kmax; ++c) img[kTabLOff + (1 << b) + c] = f2u(table_L(b, c));
     // thresholds as bit patterns; positive floats order like their bit patterns
     std::vector<uint32_t> tb(kmax);
     for (int k = 0; k < kmax; ++k) tb[k] = f2u(table_T(b, k));

@@ -22,8 +22,10 @@ struct VqEntry { uint32_t thr; uint32_t base; };
 
 // Offsets (in 32-bit words) inside the table image that stq_init uploads and every
 // workgroup copies to LDS.
-constexpr int kTabROff = 0;     // R_b[u] at kTabROff + (1<<b) - 4
-constexpr int kTabLOff = 512;   // L_b[c] at kTabLOff + (1<<b) - 4
+// R_b and L_b start at word (1<<b) of their 512-word regions, so that a code index can be OR-ed
+// onto the table's base.
+constexpr int kTabROff = 0;     // R_b[u] at kTabROff + (1<<b) + u
+constexpr int kTabLOff = 512;   // L_b[c] at kTabLOff + (1<<b) + c
 constexpr int kTabVqOff = 1024; // VqEntry table of width b at kTabVqOff + (b-2)*kVqBuckets*2
 constexpr int kTabWords = kTabVqOff + 7 * kVqBuckets * 2;
 
