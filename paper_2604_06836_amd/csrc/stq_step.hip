@@ -536,8 +536,10 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
 // -------------------------------------------------------------- step kernel
 // Every wavefront takes a contiguous range of the launch-wide tile order, so it crosses few
 // tensor boundaries and flushes its statistics once per tensor it touched.
+// The statistics variant needs about 40 more registers; it runs at two waves per SIMD instead of
+// spilling at four.
 template <bool BF16, bool STATS>
-__global__ __launch_bounds__(64 * kWavesPerGroup, 4) void step_kernel(const StepArgs a) {
+__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 4) void step_kernel(const StepArgs a) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWavesPerGroup) lds[i] = a.tables[i];
   __syncthreads();

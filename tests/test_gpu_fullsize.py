@@ -1,0 +1,107 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (all tensors of the workload in one stq_step call).
+
+The oracle cannot run 10^9 elements in seconds, but blocks are independent: for sampled windows of
+whole tiles (and every sampled tensor's ragged last tile) the inputs are copied to the host before
+the step, the oracle is run on the window alone, and codes, scales and parameters of the window are
+compared as in the small tests.  Gradient statistics of whole tensors are checked against float64
+torch reductions on the device.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_06836_amd as stq
+from workloads import configs
+from workloads.harness import DeviceModel
+
+pytestmark = pytest.mark.gpu
+
+TILE = 2048
+
+
+def sample_windows(w, rng, n_tensors=10, per_tensor=3, tiles=2):
+    """[(tensor index, first element, length)] : windows of whole tiles plus the ragged tails."""
+    L = len(w.tensors)
+    sizes = np.array([n for _, n in w.tensors])
+    picks = {int(np.argmax(sizes)), int(np.argmin(sizes)), 0, L - 1}
+    picks |= {int(i) for i in rng.choice(L, size=min(n_tensors, L), replace=False)}
+    out = []
+    for l in sorted(picks):
+        n = int(sizes[l])
+        nt = (n + TILE - 1) // TILE
+        starts = {0, max(0, nt - tiles)} | {int(x) for x in rng.integers(0, nt, size=per_tensor)}
+        for t0 in sorted(starts):
+            lo = t0 * TILE
+            out.append((l, lo, min(tiles * TILE, n - lo)))
+    return out
+
+
+def window_state(oracle, dm, w, l, lo, n):
+    """Host copy of one window of tensor l: params, grads and the unpacked oracle state."""
+    bm, bv = dm.plan[l]
+    K = w.K
+    t0, nt = lo // TILE, (n + TILE - 1) // TILE
+    th = dm.param[l][lo:lo + n].cpu().numpy().copy()
+    g = dm.grad[l][lo:lo + n]
+    g = g.view(torch.int16).cpu().numpy().view(np.uint16).copy() if g.dtype == torch.bfloat16 else g.cpu().numpy().copy()
+    mw = dm.m_codes[l][t0 * 64 * bm:(t0 + nt) * 64 * bm].cpu().numpy().view(np.uint32)
+    vw = dm.v_codes[l][t0 * 64 * bv:(t0 + nt) * 64 * bv].cpu().numpy().view(np.uint32)
+    spt = TILE // K
+    nb = (n + K - 1) // K
+    ms = dm.m_scales[l][t0 * spt:t0 * spt + nb].cpu().numpy().copy()
+    vs = dm.v_scales[l][t0 * spt:t0 * spt + nb].cpu().numpy().copy()
+    st = oracle.State(n, K, bm, bv, um=oracle.unpack(mw, n, bm), sm=ms, cv=oracle.unpack(vw, n, bv), sv=vs)
+    return th, g, st
+
+
+def check_window(oracle, dm, w, l, lo, n, th_ref, st_ref, tag):
+    bm, bv = dm.plan[l]
+    t0, nt = lo // TILE, (n + TILE - 1) // TILE
+    spt = TILE // w.K
+    mw = dm.m_codes[l][t0 * 64 * bm:(t0 + nt) * 64 * bm].cpu().numpy().view(np.uint32)
+    vw = dm.v_codes[l][t0 * 64 * bv:(t0 + nt) * 64 * bv].cpu().numpy().view(np.uint32)
+    assert np.array_equal(mw, oracle.pack(st_ref.um, bm)), f"{tag}: m codes"
+    assert np.array_equal(vw, oracle.pack(st_ref.cv, bv)), f"{tag}: v codes"
+    ms = dm.m_scales[l][t0 * spt:(t0 + nt) * spt].cpu().numpy()
+    vs = dm.v_scales[l][t0 * spt:(t0 + nt) * spt].cpu().numpy()
+    assert np.array_equal(ms.view(np.uint32), oracle.pad_scales(st_ref.sm, n, w.K).view(np.uint32)), f"{tag}: m scales"
+    assert np.array_equal(vs.view(np.uint32), oracle.pad_scales(st_ref.sv, n, w.K).view(np.uint32)), f"{tag}: v scales"
+    th = dm.param[l][lo:lo + n].cpu().numpy()
+    assert np.all(np.abs(th.astype(np.float64) - th_ref) <= 1e-6 * np.abs(th_ref)), f"{tag}: params"
+
+
+@pytest.mark.parametrize("name", ["gpt2-small", "vit-b16", "gpt2-xl", "llama7b-slice"])
+def test_full_size_sampled_parity(oracle, name):
+    w = configs.get_workload(name)
+    rng = np.random.default_rng(1234 + w.cfg)
+    plan = w.initial_plan()
+    L = len(w.tensors)
+    ctx = stq.Context(0, L)
+    dm = DeviceModel(ctx, w, plan)
+    windows = sample_windows(w, rng)
+    for t in (1, 2, 3):
+        dm.set_grads(t)
+        want_stats = t == 3
+        before = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
+        dm.step(t, stats=want_stats)
+        torch.cuda.synchronize()
+        for (l, lo, n), (th, g, st) in zip(windows, before):
+            oracle.step(th, g, st, **w.hparams, t=t)
+            check_window(oracle, dm, w, l, lo, n, th, st, f"{name} step {t} tensor {l} window {lo}+{n}")
+        if want_stats:
+            gs = ctx.stats(L, dm.stream)
+            for l in sorted({l for l, _, _ in windows}):
+                g64 = dm.grad[l].double()
+                assert gs[l].count == g64.numel()
+                assert abs(gs[l].g_sq_sum - float((g64 * g64).sum())) <= 1e-5 * float((g64 * g64).sum())
+                assert abs(gs[l].g_abs_sum - float(g64.abs().sum())) <= 1e-5 * float(g64.abs().sum())
+                assert abs(gs[l].g_sum - float(g64.sum())) <= 1e-5 * float(g64.abs().sum())
+                assert gs[l].g_absmax == float(g64.abs().max())
+                # the stored scales are the block maxima, so the maxima of the moments are the largest scales
+                assert gs[l].m_absmax == float(dm.m_scales[l].max())
+                assert gs[l].v_absmax == float(dm.v_scales[l].max())
+                assert gs[l].m_err_sq <= gs[l].m_sq_sum and gs[l].v_err_sq <= gs[l].v_sq_sum
+    ctx.close()
+    del dm
+    torch.cuda.empty_cache()
