@@ -98,15 +98,15 @@ __device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[4], uint32_t
   for (int n = 0; n < 16; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
 }
 
-// Pack the 16 codes of half h and store its words.  `carry` holds, in its upper 16 bits, the 16
+// Pack the 16 codes of half h (one byte each, four to a register) and store its words.  `carry` holds, in its upper 16 bits, the 16
 // bits the first half of an odd width leaves for the word both halves share.
 template <int B>
-__device__ __forceinline__ void pack_store(const uint32_t (&code)[16], STQ_GLOBAL uint32_t* C, uint32_t h,
+__device__ __forceinline__ void pack_store(const uint32_t (&code4)[4], STQ_GLOBAL uint32_t* C, uint32_t h,
                                            uint32_t& carry, int lane) {
   constexpr int NW = (B + 1) / 2;
   uint32_t ow[5];
 #pragma unroll
-  for (int n = 0; n < 16; ++n) insert<B>(ow, n, code[n]);
+  for (int n = 0; n < 16; ++n) insert<B>(ow, n, (code4[n >> 2] >> (8 * (n & 3))) & 0xFFu);
   if (B & 1) {
     if (h == 0) {
 #pragma unroll
@@ -229,7 +229,7 @@ __device__ __forceinline__ float updated_param(float theta, float mt, float den,
 // mq holds the quantized first moments; theta is replaced by the new parameters.
 template <bool STATS, bool TAIL, bool TABLE, bool FAST>
 __device__ __forceinline__ void quant2_update(const float (&v)[16], const float (&mq)[16], float (&theta)[16],
-                                              uint32_t (&code)[16], const float (&sn)[4], const float (&inv)[4],
+                                              uint32_t (&code4)[4], const float (&sn)[4], const float (&inv)[4],
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
                                               const uint32_t (&den_row)[4], const UpdateArgs& u, uint32_t h, int lane,
                                               uint32_t n_valid, LaneStats& st) {
@@ -242,7 +242,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[16], const float 
     const uint2 e = VQ[idx];
     uint32_t c = e.y + (bits >= e.x ? 1u : 0u);
     if (TAIL && !is_valid(n, h, lane, n_valid)) c = 0;
-    code[n] = c;
+    if ((n & 3) == 0) code4[i] = c; else code4[i] |= c << (8 * (n & 3));
     if (STATS) {
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       if (TAIL && !is_valid(n, h, lane, n_valid)) vq = 0.0f;
@@ -468,7 +468,7 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
     const int qmax = (1 << (bm - 1)) - 1;
     const float qmaxf = static_cast<float>(qmax);
     const uint32_t r_base = 4u << bm;
-    uint32_t code[16];
+    uint32_t code4[4];
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
       const int i = n >> 2;
@@ -479,7 +479,7 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
       q = min(max(q, 0), 2 * qmax);
       uint32_t u = static_cast<uint32_t>(q);
       if (TAIL && !is_valid(n, h, lane, n_valid)) u = 0;
-      code[n] = u;
+      if ((n & 3) == 0) code4[i] = u; else code4[i] |= u << (8 * (n & 3));
       float mq = sn[i] * lds_at(Rreg, (u << 2) | r_base);
       if (STATS) {
         if (TAIL && !is_valid(n, h, lane, n_valid)) mq = 0.0f;
@@ -490,7 +490,7 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
       }
       m[n] = mq;
     }
-    STQ_SWITCH_BITS(bm, (pack_store<B>(code, CM, h, carry_m, lane)));
+    STQ_SWITCH_BITS(bm, (pack_store<B>(code4, CM, h, carry_m, lane)));
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
@@ -508,16 +508,16 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bv);
-    uint32_t code[16];
+    uint32_t code4[4];
     if (use_table) {
       if (fast_div)
-        quant2_update<STATS, TAIL, true, true>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, true>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
       else
-        quant2_update<STATS, TAIL, true, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
     } else {
-      quant2_update<STATS, TAIL, false, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+      quant2_update<STATS, TAIL, false, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
     }
-    STQ_SWITCH_BITS(bv, (pack_store<B>(code, CV, h, carry_v, lane)));
+    STQ_SWITCH_BITS(bv, (pack_store<B>(code4, CV, h, carry_v, lane)));
   }
 
 #pragma unroll

@@ -69,6 +69,7 @@ def check_window(oracle, dm, w, l, lo, n, th_ref, st_ref, tag):
     assert np.array_equal(vs.view(np.uint32), oracle.pad_scales(st_ref.sv, n, w.K).view(np.uint32)), f"{tag}: v scales"
     th = dm.param[l][lo:lo + n].cpu().numpy()
     assert np.all(np.abs(th.astype(np.float64) - th_ref) <= 1e-6 * np.abs(th_ref)), f"{tag}: params"
+    assert np.array_equal(th.view(np.uint32), th_ref.view(np.uint32)), f"{tag}: params not bit-equal"
 
 
 @pytest.mark.parametrize("name", ["gpt2-small", "vit-b16", "gpt2-xl", "llama7b-slice"])

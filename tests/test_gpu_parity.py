@@ -39,6 +39,9 @@ def assert_tensor_parity(oracle, dm, l, th_ref, st_ref, tag=""):
     assert np.array_equal(vs.view(np.uint32), oracle.pad_scales(st_ref.sv, n, K).view(np.uint32)), f"{tag} v scales {l}"
     err = np.abs(th.astype(np.float64) - th_ref)
     assert np.all(err <= PARAM_RTOL * np.abs(th_ref)), f"{tag} params tensor {l}: max rel {np.max(err / np.maximum(np.abs(th_ref), 1e-30))}"
+    # stronger than the bar: the kernel's square root and quotient are correctly rounded like the
+    # oracle's, so the parameters agree bit for bit
+    assert np.array_equal(th.view(np.uint32), th_ref.view(np.uint32)), f"{tag} params tensor {l}: {np.count_nonzero(th != th_ref)} not bit-equal"
 
 
 def run_both(oracle, ctx, w, plan, steps, stats_steps=(), tag=""):
