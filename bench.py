@@ -50,6 +50,19 @@ def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2):
             "sample": "first %d parameters of the workload (%d tensors), %d steps, %.1f s" % (acc, len(sample), steps, dt)}
 
 
+def copy_calibration(torch, n=1 << 28, launches=5):
+    """dst = src + 1 over 2^28 fp32 elements: each launch reads n*4 bytes and writes n*4 bytes.
+    A profiler's HBM byte counters for this kernel give the factor that scales them to bytes."""
+    src = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(launches):
+        torch.add(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration": True, "kernel": "elementwise add", "launches": launches,
+                      "read_bytes_per_launch": n * 4, "write_bytes_per_launch": n * 4}))
+
+
 def calibrate_ladder(scores, probs):
     """Thresholds at the score quantiles that give the widths the target frequencies."""
     import numpy as np
@@ -64,6 +77,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain elementwise kernel of known size (scale reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
@@ -78,6 +93,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU (and libstq.so built for gfx950)")
+    if args.copy_calibration:
+        return copy_calibration(torch)
     stq.load_library()  # fails loudly if the HIP library is missing
     w = configs.get_workload(args.workload)
     steps = args.steps if args.steps is not None else w.steps
@@ -169,7 +186,7 @@ def main():
                      "kernel_ms_avg": k_avg_ms, "algorithmic_bytes_per_param": bpp,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
-    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    traffic_file = os.path.join(ROOT, "profiles", "step_kernel_traffic.json")
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file)).get(w.name)
         if tr:

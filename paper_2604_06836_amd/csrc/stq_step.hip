@@ -6,13 +6,15 @@
 // Arithmetic contract: IEEE binary32, every operation rounded on its own (build with
 // -ffp-contract=off); division and square root are the correctly rounded ones.
 //
-// Work decomposition: one wavefront owns one 2048-element tile at a time and processes it as two
-// halves of 4 rows.  In row i lane j holds the 4 elements 256*i + 4*j + e, so every parameter and
-// gradient access is a coalesced 16-byte (8-byte for bf16) per-lane access, and a block of
-// K = 64/128/256 consecutive elements is 16/32/64 neighbouring lanes of one row.  The lane's 32
-// codes of a state are exactly b 32-bit words; word p of all lanes is one contiguous 256-byte row
-// of the code buffer.  A half uses the words that hold its 16 codes (the middle word of an odd
-// width is written by the second half, the first half hands its 16 bits over in a register).
+// Work decomposition: one wavefront owns one 2048-element tile at a time and processes it as four
+// quarters of 2 rows: a quarter's working set fits the 128 registers of four waves per SIMD with
+// nothing spilled to scratch memory, so the kernel's HBM traffic is the algorithmic traffic.
+// In row i lane j holds the 4 elements 256*i + 4*j + e, so
+// every parameter and gradient access is a coalesced 16-byte (8-byte for bf16) per-lane access,
+// and a block of K = 64/128/256 consecutive elements is 16/32/64 neighbouring lanes of one row.
+// The lane's 32 codes of a state are exactly b 32-bit words; word p of all lanes is one contiguous
+// 256-byte row of the code buffer.  A quarter reads the words that hold its 8 codes and writes
+// the words it completes; the bits of a word shared with the next quarter travel in a register.
 //
 // Only the bit-stream unpack and pack are specialised per width (small switch arms); all
 // arithmetic is width-generic and takes the width through table offsets and constants.
@@ -30,11 +32,11 @@ namespace stq {
 namespace {
 
 constexpr int XS = 68;  // row stride (words) of the transpose scratch: keeps 16-byte alignment, shifts banks
-// per-wave LDS scratch: XR[8][XS] partial maxima (later the den table), old scales, new scales, reciprocals
-constexpr int kWaveScratch = 8 * XS + 3 * 64;
+// per-wave LDS scratch: XR[4][XS] partial maxima (later the den table), old scales, new scales, reciprocals
+constexpr int kWaveScratch = 4 * XS + 3 * 64;
 constexpr int kLdsWords = kTabWords + kWavesPerGroup * kWaveScratch;
 constexpr int kStatFlushTiles = 16;  // fp32 lane sums are widened to fp64 every this many tiles
-constexpr uint32_t kDenEntries = 256;  // capacity of the per-wave den table (8 bytes per entry, inside XR)
+constexpr uint32_t kDenEntries = 128;  // capacity of the per-wave den table (8 bytes per entry, inside XR)
 
 // Pointers that arrive through the tensor table are loaded from memory, so the compiler cannot
 // see that they are global; say so, to get global_load/global_store instead of flat accesses.
@@ -61,9 +63,10 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // ---------------------------------------------------------------- bit streams
-// Within a half, code n (0..15) of width B sits at bits [n*B, n*B+B) of the half's local stream.
+// Within a quarter, code n (0..7) of width B sits at bits [n*B, n*B+B) of the quarter's local stream
+// (at most 64 bits, words w[0], w[1]).
 template <int B>
-__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[5], int n) {
+__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[3], int n) {
   const int off = n * B, p = off >> 5, sh = off & 31;
   constexpr uint32_t mask = (1u << B) - 1u;
   if (sh + B <= 32) return (w[p] >> sh) & mask;
@@ -71,58 +74,43 @@ __device__ __forceinline__ uint32_t extract(const uint32_t (&w)[5], int n) {
 }
 
 template <int B>
-__device__ __forceinline__ void insert(uint32_t (&w)[5], int n, uint32_t code) {
+__device__ __forceinline__ void insert(uint32_t (&w)[3], int n, uint32_t code) {
   const int off = n * B, p = off >> 5, sh = off & 31;
   if (sh == 0) w[p] = code; else w[p] |= code << sh;
   if (sh + B > 32) w[p + 1] = code >> (32 - sh);  // first bits of the next word
 }
 
-// The 16 codes of half h as byte offsets into the width's value table: (code << 2) | (4 << B).
-// lw holds the words (h*B)>>1 .. of the lane's B words; for an odd width the second half starts
-// 16 bits into its first word.
+// The 8 codes of a quarter as byte offsets into the width's value table: (code << 2) | (4 << B).
+// lw holds the lane's words from the one that contains the quarter's first bit; s0 (0, 8, 16 or
+// 24) is the position of that bit in lw[0].
 template <int B>
-__device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[4], uint32_t h, uint32_t (&off)[16]) {
-  constexpr int NW = (B + 1) / 2;
-  uint32_t w[5];
-  if (B & 1) {
-    const uint32_t s0 = h * 16u;
+__device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[3], uint32_t s0, uint32_t (&off)[8]) {
+  uint32_t w[3];
+  w[0] = __builtin_amdgcn_alignbit(lw[1], lw[0], s0);
+  w[1] = __builtin_amdgcn_alignbit(lw[2], lw[1], s0);
+  w[2] = 0u;
 #pragma unroll
-    for (int k = 0; k < NW; ++k)
-      w[k] = __builtin_amdgcn_alignbit(k + 1 < NW ? lw[k + 1] : 0u, lw[k], s0);
-  } else {
-#pragma unroll
-    for (int k = 0; k < NW; ++k) w[k] = lw[k];
-  }
-  w[NW] = 0u;
-#pragma unroll
-  for (int n = 0; n < 16; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
+  for (int n = 0; n < 8; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
 }
 
-// Pack the 16 codes of half h (one byte each, four to a register) and store its words.  `carry` holds, in its upper 16 bits, the 16
-// bits the first half of an odd width leaves for the word both halves share.
+// Pack the 8 codes of a quarter (one byte each, four to a register) behind the s0 bits that
+// `carry` holds of the current word, store the words this completes (at C, word stride 64) and
+// keep the rest in `carry`.
 template <int B>
-__device__ __forceinline__ void pack_store(const uint32_t (&code4)[4], STQ_GLOBAL uint32_t* C, uint32_t h,
+__device__ __forceinline__ void pack_store(const uint32_t (&code4)[2], STQ_GLOBAL uint32_t* C, uint32_t s0,
                                            uint32_t& carry, int lane) {
-  constexpr int NW = (B + 1) / 2;
-  uint32_t ow[5];
+  uint32_t ow[3] = {0u, 0u, 0u};
 #pragma unroll
-  for (int n = 0; n < 16; ++n) insert<B>(ow, n, (code4[n >> 2] >> (8 * (n & 3))) & 0xFFu);
-  if (B & 1) {
-    if (h == 0) {
-#pragma unroll
-      for (int k = 0; k < NW - 1; ++k) C[k * 64 + lane] = ow[k];
-      carry = ow[NW - 1] << 16;
-    } else {
-      STQ_GLOBAL uint32_t* C1 = C + (B / 2) * 64;
-#pragma unroll
-      for (int k = 0; k < NW; ++k)
-        C1[k * 64 + lane] = __builtin_amdgcn_alignbit(ow[k], k == 0 ? carry : ow[k - 1], 16);
-    }
-  } else {
-    STQ_GLOBAL uint32_t* C1 = C + h * (B / 2) * 64;
-#pragma unroll
-    for (int k = 0; k < NW; ++k) C1[k * 64 + lane] = ow[k];
-  }
+  for (int n = 0; n < 8; ++n) insert<B>(ow, n, (code4[n >> 2] >> (8 * (n & 3))) & 0xFFu);
+  const unsigned long long x = (static_cast<unsigned long long>(ow[1]) << 32) | ow[0];
+  const unsigned long long lo = x << s0;
+  const uint32_t m0 = carry | static_cast<uint32_t>(lo);
+  const uint32_t m1 = static_cast<uint32_t>(lo >> 32);
+  const uint32_t m2 = s0 ? (ow[1] >> (32u - s0)) : 0u;
+  const uint32_t done = (s0 + 8u * B) >> 5;  // complete words: 0, 1 or 2
+  if (done >= 1) C[lane] = m0;
+  if (done >= 2) C[64 + lane] = m1;
+  carry = done == 0 ? m0 : (done == 1 ? m1 : m2);
 }
 
 #define STQ_SWITCH_BITS(bits, CALL)               \
@@ -136,9 +124,9 @@ __device__ __forceinline__ void pack_store(const uint32_t (&code4)[4], STQ_GLOBA
     default: { constexpr int B = 8; CALL; } break; \
   }
 
-// element n (0..15) of this lane in half h is real (not pad) in a tile with n_valid elements
-__device__ __forceinline__ bool is_valid(int n, uint32_t h, int lane, uint32_t n_valid) {
-  return (1024u * h + static_cast<uint32_t>(256 * (n >> 2) + 4 * lane + (n & 3))) < n_valid;
+// element n (0..7) of this lane in quarter q is real (not pad) in a tile with n_valid elements
+__device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n_valid) {
+  return (512u * q + static_cast<uint32_t>(256 * (n >> 2) + 4 * lane + (n & 3))) < n_valid;
 }
 
 // -------------------------------------------------------------------- statistics
@@ -228,24 +216,24 @@ __device__ __forceinline__ float updated_param(float theta, float mt, float den,
 // the per-wave table DEN, indexed by (row, block, code); otherwise they are computed per element.
 // mq holds the quantized first moments; theta is replaced by the new parameters.
 template <bool STATS, bool TAIL, bool TABLE, bool FAST>
-__device__ __forceinline__ void quant2_update(const float (&v)[16], const float (&mq)[16], float (&theta)[16],
-                                              uint32_t (&code4)[4], const float (&sn)[4], const float (&inv)[4],
+__device__ __forceinline__ void quant2_update(const float (&v)[8], const float (&mq)[8], float (&theta)[8],
+                                              uint32_t (&code4)[2], const float (&sn)[2], const float (&inv)[2],
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
-                                              const uint32_t (&den_row)[4], const UpdateArgs& u, uint32_t h, int lane,
+                                              const uint32_t (&den_row)[2], const UpdateArgs& u, uint32_t q, int lane,
                                               uint32_t n_valid, LaneStats& st) {
 #pragma unroll
-  for (int n = 0; n < 16; ++n) {
+  for (int n = 0; n < 8; ++n) {
     const int i = n >> 2;
     const float rho = v[n] * inv[i];
     const uint32_t bits = f2u(rho);
     const uint32_t idx = min(kVqTop - (bits >> kVqShift), static_cast<uint32_t>(kVqBuckets - 1));
     const uint2 e = VQ[idx];
     uint32_t c = e.y + (bits >= e.x ? 1u : 0u);
-    if (TAIL && !is_valid(n, h, lane, n_valid)) c = 0;
+    if (TAIL && !is_valid(n, q, lane, n_valid)) c = 0;
     if ((n & 3) == 0) code4[i] = c; else code4[i] |= c << (8 * (n & 3));
     if (STATS) {
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
-      if (TAIL && !is_valid(n, h, lane, n_valid)) vq = 0.0f;
+      if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
       const float d = v[n] - vq;
       st.v_sum += v[n];
       st.v_sq += v[n] * v[n];
@@ -264,13 +252,13 @@ __device__ __forceinline__ void quant2_update(const float (&v)[16], const float 
   }
 }
 
-// ------------------------------------------------------------------ one half tile
-// Lane L = (value vL = L&7, lane group qL = L>>3) owns one (state, row) pair's block scale:
-// state = vL>>2, row = 4h + (vL&3), block within the row = qL >> (lgK-5).
+// ------------------------------------------------------------------ one quarter tile
+// Lane L = (value vL = L&3, lane group qL = L>>2) owns one (state, row) pair's block scale:
+// state = vL>>1, row = 2q + (vL&1), block within the row = qL >> (lgK-4).
 template <bool BF16, bool STATS, bool TAIL>
-__device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile, uint32_t h, uint32_t n_valid,
-                                             const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
-                                             uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
+__device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t tile, uint32_t q, uint32_t n_valid,
+                                                const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
+                                                uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
   // Everything derived from the lane index and the block size is cheap to recompute.  Hide the two
   // from loop-invariant code motion, which would otherwise keep dozens of such values live across
   // the whole tile loop and spill them.
@@ -278,34 +266,34 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
   uint32_t lgK = a.lgK;
   asm volatile("" : "+s"(lgK));
   const uint32_t bm = d.bm, bv = d.bv;
-  const size_t e0 = static_cast<size_t>(tile) * kTile + 1024u * h;
+  const size_t e0 = static_cast<size_t>(tile) * kTile + 512u * q;
   STQ_GLOBAL float* P = as_global(d.param + e0);
-  STQ_GLOBAL uint32_t* CM = as_global(d.m_codes + static_cast<size_t>(tile) * 64u * bm);
-  STQ_GLOBAL uint32_t* CV = as_global(d.v_codes + static_cast<size_t>(tile) * 64u * bv);
+  // the quarter's first bit: word (q*b)>>2 of the lane's b words, bit 8*((q*b)&3)
+  const uint32_t s0m = 8u * ((q * bm) & 3u), s0v = 8u * ((q * bv) & 3u);
+  STQ_GLOBAL uint32_t* CM = as_global(d.m_codes + static_cast<size_t>(tile) * 64u * bm) + ((q * bm) >> 2) * 64;
+  STQ_GLOBAL uint32_t* CV = as_global(d.v_codes + static_cast<size_t>(tile) * 64u * bv) + ((q * bv) >> 2) * 64;
   const size_t sbase = static_cast<size_t>(tile) << (11 - lgK);  // scales per tile = 2048/K
-  const int vL = lane & 7, qL = lane >> 3;
-  const uint32_t sidx = ((4u * h + static_cast<uint32_t>(vL & 3)) << (8 - lgK)) + (static_cast<uint32_t>(qL) >> (lgK - 5));
-  STQ_GLOBAL float* SC = as_global((vL >> 2) ? d.v_scales : d.m_scales);
+  const int vL = lane & 3, qL = lane >> 2;
+  const uint32_t sidx = ((2u * q + static_cast<uint32_t>(vL & 1)) << (8 - lgK)) + (static_cast<uint32_t>(qL) >> (lgK - 4));
+  STQ_GLOBAL float* SC = as_global((vL >> 1) ? d.v_scales : d.m_scales);
 
   // ---- loads for the moment phase --------------------------------------------
   const float sc_old = SC[sbase + sidx];
-  uint32_t lwm[4], lwv[4];  // the code words of this half: words (h*b)>>1 .. of the lane's b words
+  uint32_t lwm[3], lwv[3];
   {
-    const uint32_t nwm = (bm + 1) >> 1, nwv = (bv + 1) >> 1;
-    STQ_GLOBAL const uint32_t* cm = CM + ((h * bm) >> 1) * 64 + lane;
-    STQ_GLOBAL const uint32_t* cv = CV + ((h * bv) >> 1) * 64 + lane;
+    const uint32_t nwm = (s0m + 8u * bm + 31u) >> 5, nwv = (s0v + 8u * bv + 31u) >> 5;  // 1..3 words
 #pragma unroll
-    for (int k = 0; k < 4; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? cm[k * 64] : 0u;
+    for (int k = 0; k < 3; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? CM[k * 64 + lane] : 0u;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? cv[k * 64] : 0u;
+    for (int k = 0; k < 3; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? CV[k * 64 + lane] : 0u;
   }
-  float g[16];
+  float g[8];
   {
     STQ_GLOBAL const float* G32 = as_global(static_cast<const float*>(d.grad) + e0);
     STQ_GLOBAL const uint16_t* G16 = as_global(static_cast<const uint16_t*>(d.grad) + e0);
     if (!TAIL) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < 2; ++i) {
         if (BF16) {
           const u32x2 r = reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[lane];
           g[4 * i + 0] = u2f(r.x << 16); g[4 * i + 1] = u2f(r.x & 0xFFFF0000u);
@@ -317,9 +305,9 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
       }
     } else {
 #pragma unroll
-      for (int n = 0; n < 16; ++n) {
+      for (int n = 0; n < 8; ++n) {
         float x = 0.0f;
-        if (is_valid(n, h, lane, n_valid)) {
+        if (is_valid(n, q, lane, n_valid)) {
           const int idx = 256 * (n >> 2) + 4 * lane + (n & 3);
           x = BF16 ? u2f(static_cast<uint32_t>(G16[idx]) << 16) : G32[idx];
         }
@@ -328,25 +316,23 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
     }
   }
 
-  // old scales to every lane that needs them: lane j reads the 8 values of its lane group
+  // old scales to every lane that needs them: lane j reads the 4 values of its lane group
   float* wsf = reinterpret_cast<float*>(ws);
-  float* XR = wsf;                // [8][XS]
-  float* SO = wsf + 8 * XS;       // [64] old scales by owner lane
+  float* XR = wsf;                // [4][XS]
+  float* SO = wsf + 4 * XS;       // [64] old scales by owner lane
   float* SN = SO + 64;            // [64] new scales
   float* SI = SN + 64;            // [64] reciprocals of the new scales
   SO[lane] = sc_old;
   wave_lds_sync();
-  float som[4], sov[4];
+  float som[2], sov[2];
   {
-    const float4* s4 = reinterpret_cast<const float4*>(SO + (lane >> 3) * 8);
-    const float4 a0 = s4[0], a1 = s4[1];
-    som[0] = a0.x; som[1] = a0.y; som[2] = a0.z; som[3] = a0.w;
-    sov[0] = a1.x; sov[1] = a1.y; sov[2] = a1.z; sov[3] = a1.w;
+    const float4 a0 = *reinterpret_cast<const float4*>(SO + (lane >> 2) * 4);
+    som[0] = a0.x; som[1] = a0.y; sov[0] = a0.z; sov[1] = a0.w;
   }
 
   if (STATS) {
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
+    for (int n = 0; n < 8; ++n) {
       st.g_sum += g[n];
       st.g_abs += fabsf(g[n]);
       st.g_sq += g[n] * g[n];
@@ -357,19 +343,19 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
   // ---- moments: m_t = beta1*m_{t-1} + (1-beta1)*g ; v_t = beta2*v_{t-1} + (1-beta2)*g^2 ----
   const float* Rreg = reinterpret_cast<const float*>(lds) + kTabROff;  // value tables, see stq_tables.h
   const float* Lreg = reinterpret_cast<const float*>(lds) + kTabLOff;
-  float m[16], v[16];
+  float m[8], v[8];
   {
-    uint32_t off[16];
-    STQ_SWITCH_BITS(bm, (unpack_offsets<B>(lwm, h, off)));
+    uint32_t off[8];
+    STQ_SWITCH_BITS(bm, (unpack_offsets<B>(lwm, s0m, off)));
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
+    for (int n = 0; n < 8; ++n) {
       const float mh = som[n >> 2] * lds_at(Rreg, off[n]);
       const float x = a.beta1 * mh, y = a.omb1 * g[n];
       m[n] = x + y;
     }
-    STQ_SWITCH_BITS(bv, (unpack_offsets<B>(lwv, h, off)));
+    STQ_SWITCH_BITS(bv, (unpack_offsets<B>(lwv, s0v, off)));
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
+    for (int n = 0; n < 8; ++n) {
       const float vh = sov[n >> 2] * lds_at(Lreg, off[n]);
       const float gg = g[n] * g[n];
       const float x = a.beta2 * vh, y = a.omb2 * gg;
@@ -378,58 +364,58 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
   }
   if (TAIL) {
 #pragma unroll
-    for (int n = 0; n < 16; ++n)
-      if (!is_valid(n, h, lane, n_valid)) { m[n] = 0.0f; v[n] = 0.0f; }
+    for (int n = 0; n < 8; ++n)
+      if (!is_valid(n, q, lane, n_valid)) { m[n] = 0.0f; v[n] = 0.0f; }
   }
 
   // ---- parameters: issued here so that they arrive while the block maxima are reduced ----
-  float theta[16];
+  float theta[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
       const f32x4 t = reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[lane];
       theta[4 * i] = t.x; theta[4 * i + 1] = t.y; theta[4 * i + 2] = t.z; theta[4 * i + 3] = t.w;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        theta[4 * i + e] = is_valid(4 * i + e, h, lane, n_valid) ? P[256 * i + 4 * lane + e] : 0.0f;
+        theta[4 * i + e] = is_valid(4 * i + e, q, lane, n_valid) ? P[256 * i + 4 * lane + e] : 0.0f;
     }
   }
 
   // ---- block maxima: lane partials -> LDS transpose -> one owner lane per (state,row,block)
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     const float pm = fmaxf(fmaxf(fabsf(m[4 * i]), fabsf(m[4 * i + 1])), fmaxf(fabsf(m[4 * i + 2]), fabsf(m[4 * i + 3])));
     const float pv = fmaxf(fmaxf(v[4 * i], v[4 * i + 1]), fmaxf(v[4 * i + 2], v[4 * i + 3]));
     XR[i * XS + lane] = pm;
-    XR[(4 + i) * XS + lane] = pv;
+    XR[(2 + i) * XS + lane] = pv;
   }
   wave_lds_sync();
   float r;
   {
-    const float4* x4 = reinterpret_cast<const float4*>(XR + vL * XS + qL * 8);
-    const float4 t0 = x4[0], t1 = x4[1];
-    r = fmaxf(fmaxf(fmaxf(t0.x, t0.y), fmaxf(t0.z, t0.w)), fmaxf(fmaxf(t1.x, t1.y), fmaxf(t1.z, t1.w)));
+    const float4 t0 = *reinterpret_cast<const float4*>(XR + vL * XS + qL * 4);
+    r = fmaxf(fmaxf(t0.x, t0.y), fmaxf(t0.z, t0.w));
   }
+  r = fmaxf(r, __shfl_xor(r, 4, 64));
   r = fmaxf(r, __shfl_xor(r, 8, 64));
   if (lgK >= 7) r = fmaxf(r, __shfl_xor(r, 16, 64));
   if (lgK == 8) r = fmaxf(r, __shfl_xor(r, 32, 64));
   if (STATS) {
-    if (vL < 4) st.m_max = fmaxf(st.m_max, r); else st.v_max = fmaxf(st.v_max, r);
+    if (vL < 2) st.m_max = fmaxf(st.m_max, r); else st.v_max = fmaxf(st.v_max, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
   const float sc_inv = (sc_new > 0.0f) ? 1.0f / sc_new : 0.0f;
   SN[lane] = sc_new;
   SI[lane] = sc_inv;
-  if ((static_cast<uint32_t>(qL) & ((1u << (lgK - 5)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
+  if ((static_cast<uint32_t>(qL) & ((1u << (lgK - 4)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
   wave_lds_sync();
 
   // ---- table of den = sqrt(vq*ibc2) + eps and 1/den per (row, block, second-moment code) ----
-  // Used when a level serves at least four elements: entries = (1024/K) << bv <= 256.  The table
+  // Used when a level serves at least four elements: entries = (512/K) << bv <= 128.  The table
   // takes the place of XR, whose last readers have finished.
   const UpdateArgs ua = {a.ibc1, a.ibc2, a.eps, a.lr, a.decay};
-  const uint32_t n_entries = (1024u >> lgK) << bv;
+  const uint32_t n_entries = (512u >> lgK) << bv;
   const bool use_table = n_entries <= kDenEntries;
   const uint32_t l_base = 4u << bv;
   float2* DEN = reinterpret_cast<float2*>(XR);
@@ -437,14 +423,14 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
   if (use_table) {
     // the fast quotient needs every operand in a range where no residual underflows or overflows
     bool bad = false;
-    if (vL < 4) {
+    if (vL < 2) {
       const float x = sc_new * a.ibc1;
       bad = !(sc_new == 0.0f || (x >= 0x1p-40f && x <= 0x1p40f));
     }
     for (uint32_t e = lane; e < n_entries; e += 64) {
       const uint32_t c = e & ((1u << bv) - 1u), rg = e >> bv;
       const uint32_t row = rg >> (8 - lgK), blk = rg & ((1u << (8 - lgK)) - 1u);
-      const float sv = SN[((blk << (lgK - 5)) << 3) + 4 + row];
+      const float sv = SN[((blk << (lgK - 4)) << 2) + 2 + row];
       const float vq = sv * lds_at(Lreg, (c << 2) | l_base);
       const float vt = vq * a.ibc2;
       const float den = __builtin_sqrtf(vt) + a.eps;
@@ -458,31 +444,30 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
 
   // ---- linear symmetric quantization of m; m is replaced by its quantized value ----
   {
-    float sn[4], inv[4];
+    float sn[2], inv[2];
     {
-      const float4 a0 = *reinterpret_cast<const float4*>(SN + (lane >> 3) * 8);
-      const float4 b0 = *reinterpret_cast<const float4*>(SI + (lane >> 3) * 8);
-      sn[0] = a0.x; sn[1] = a0.y; sn[2] = a0.z; sn[3] = a0.w;
-      inv[0] = b0.x; inv[1] = b0.y; inv[2] = b0.z; inv[3] = b0.w;
+      const float4 a0 = *reinterpret_cast<const float4*>(SN + (lane >> 2) * 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(SI + (lane >> 2) * 4);
+      sn[0] = a0.x; sn[1] = a0.y; inv[0] = b0.x; inv[1] = b0.y;
     }
     const int qmax = (1 << (bm - 1)) - 1;
     const float qmaxf = static_cast<float>(qmax);
     const uint32_t r_base = 4u << bm;
-    uint32_t code4[4];
+    uint32_t code4[2];
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
+    for (int n = 0; n < 8; ++n) {
       const int i = n >> 2;
       const float t = (m[n] * inv[i]) * qmaxf;
       // round half to even: adding 1.5*2^23 leaves the integer in the low mantissa bits (|t| <= 127.5)
       const float rr = t + 12582912.0f;
-      int q = static_cast<int>(f2u(rr)) - (0x4B400000 - qmax);
-      q = min(max(q, 0), 2 * qmax);
-      uint32_t u = static_cast<uint32_t>(q);
-      if (TAIL && !is_valid(n, h, lane, n_valid)) u = 0;
+      int qq = static_cast<int>(f2u(rr)) - (0x4B400000 - qmax);
+      qq = min(max(qq, 0), 2 * qmax);
+      uint32_t u = static_cast<uint32_t>(qq);
+      if (TAIL && !is_valid(n, q, lane, n_valid)) u = 0;
       if ((n & 3) == 0) code4[i] = u; else code4[i] |= u << (8 * (n & 3));
       float mq = sn[i] * lds_at(Rreg, (u << 2) | r_base);
       if (STATS) {
-        if (TAIL && !is_valid(n, h, lane, n_valid)) mq = 0.0f;
+        if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
         const float dd = m[n] - mq;
         st.m_sum += m[n];
         st.m_sq += m[n] * m[n];
@@ -490,45 +475,44 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
       }
       m[n] = mq;
     }
-    STQ_SWITCH_BITS(bm, (pack_store<B>(code4, CM, h, carry_m, lane)));
+    STQ_SWITCH_BITS(bm, (pack_store<B>(code4, CM, s0m, carry_m, lane)));
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
   {
-    float sn[4], inv[4];
+    float sn[2], inv[2];
     {
-      const float4 a1 = *reinterpret_cast<const float4*>(SN + (lane >> 3) * 8 + 4);
-      const float4 b1 = *reinterpret_cast<const float4*>(SI + (lane >> 3) * 8 + 4);
-      sn[0] = a1.x; sn[1] = a1.y; sn[2] = a1.z; sn[3] = a1.w;
-      inv[0] = b1.x; inv[1] = b1.y; inv[2] = b1.z; inv[3] = b1.w;
+      const float4 a1 = *reinterpret_cast<const float4*>(SN + (lane >> 2) * 4);
+      const float4 b1 = *reinterpret_cast<const float4*>(SI + (lane >> 2) * 4);
+      sn[0] = a1.z; sn[1] = a1.w; inv[0] = b1.z; inv[1] = b1.w;
     }
     const uint2* VQ = reinterpret_cast<const uint2*>(lds + kTabVqOff) + (bv - 2) * kVqBuckets;
     // den table entry ((row*G + block) << bv) + c, G = 256/K blocks per row
-    uint32_t den_row[4];
+    uint32_t den_row[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
       den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bv);
-    uint32_t code4[4];
+    uint32_t code4[2];
     if (use_table) {
       if (fast_div)
-        quant2_update<STATS, TAIL, true, true>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, true>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
       else
-        quant2_update<STATS, TAIL, true, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
     } else {
-      quant2_update<STATS, TAIL, false, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, h, lane, n_valid, st);
+      quant2_update<STATS, TAIL, false, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
     }
-    STQ_SWITCH_BITS(bv, (pack_store<B>(code4, CV, h, carry_v, lane)));
+    STQ_SWITCH_BITS(bv, (pack_store<B>(code4, CV, s0v, carry_v, lane)));
   }
 
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
       reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[lane] =
           f32x4{theta[4 * i], theta[4 * i + 1], theta[4 * i + 2], theta[4 * i + 3]};
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (is_valid(4 * i + e, h, lane, n_valid)) P[256 * i + 4 * lane + e] = theta[4 * i + e];
+        if (is_valid(4 * i + e, q, lane, n_valid)) P[256 * i + 4 * lane + e] = theta[4 * i + e];
     }
   }
 }
@@ -536,8 +520,7 @@ __device__ __forceinline__ void process_half(const TensorDesc& d, uint32_t tile,
 // -------------------------------------------------------------- step kernel
 // Every wavefront takes a contiguous range of the launch-wide tile order, so it crosses few
 // tensor boundaries and flushes its statistics once per tensor it touched.
-// The statistics variant needs about 40 more registers; it runs at two waves per SIMD instead of
-// spilling at four.
+// The statistics variant needs about 40 more registers and runs at a lower occupancy.
 template <bool BF16, bool STATS>
 __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 4) void step_kernel(const StepArgs a) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
@@ -572,13 +555,13 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 4) void step_kerne
       uint32_t carry_m = 0, carry_v = 0;
       if (left >= static_cast<uint64_t>(kTile)) {
 #pragma nounroll
-        for (uint32_t h = 0; h < 2; ++h)
-          process_half<BF16, STATS, false>(d, tile, h, kTile, a, lds, ws, lane, carry_m, carry_v, st);
+        for (uint32_t q = 0; q < 4; ++q)
+          process_quarter<BF16, STATS, false>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
       } else {
 #pragma nounroll
-        for (uint32_t h = 0; h < 2; ++h)
-          process_half<BF16, STATS, true>(d, tile, h, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
-                                          carry_v, st);
+        for (uint32_t q = 0; q < 4; ++q)
+          process_quarter<BF16, STATS, true>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
+                                             carry_v, st);
       }
       if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
     }
