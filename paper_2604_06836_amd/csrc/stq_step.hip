@@ -93,15 +93,14 @@ __device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[3], uint32_t
   for (int n = 0; n < 8; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
 }
 
-// Pack the 8 codes of a quarter (one byte each, four to a register) behind the s0 bits that
-// `carry` holds of the current word, store the words this completes (at C, word stride 64) and
-// keep the rest in `carry`.
+// Pack the 8 codes of a quarter behind the s0 bits that `carry` holds of the current word, store
+// the words this completes (at C, word stride 64) and keep the rest in `carry`.
 template <int B>
-__device__ __forceinline__ void pack_store(const uint32_t (&code4)[2], STQ_GLOBAL uint32_t* C, uint32_t s0,
-                                           uint32_t& carry, int lane) {
+__device__ __forceinline__ void pack_store(const uint32_t (&code)[8], STQ_GLOBAL uint32_t* C, uint32_t s0,
+                                           uint32_t& carry, uint32_t lane) {
   uint32_t ow[3] = {0u, 0u, 0u};
 #pragma unroll
-  for (int n = 0; n < 8; ++n) insert<B>(ow, n, (code4[n >> 2] >> (8 * (n & 3))) & 0xFFu);
+  for (int n = 0; n < 8; ++n) insert<B>(ow, n, code[n]);
   const unsigned long long x = (static_cast<unsigned long long>(ow[1]) << 32) | ow[0];
   const unsigned long long lo = x << s0;
   const uint32_t m0 = carry | static_cast<uint32_t>(lo);
@@ -109,7 +108,7 @@ __device__ __forceinline__ void pack_store(const uint32_t (&code4)[2], STQ_GLOBA
   const uint32_t m2 = s0 ? (ow[1] >> (32u - s0)) : 0u;
   const uint32_t done = (s0 + 8u * B) >> 5;  // complete words: 0, 1 or 2
   if (done >= 1) C[lane] = m0;
-  if (done >= 2) C[64 + lane] = m1;
+  if (done >= 2) C[64u + lane] = m1;
   carry = done == 0 ? m0 : (done == 1 ? m1 : m2);
 }
 
@@ -183,6 +182,58 @@ __device__ __forceinline__ void flush_stats(LaneStats& s, double* slot, int lane
   s.clear_all();
 }
 
+// x from the lane that a DPP control word names (all lanes of the wave active)
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16 lanes
+
+// Correctly rounded square root for x = 0 or 2^-96 <= x <= 2^96: the hardware estimate is within
+// one ulp; the residuals x - next_down*s and x - next_up*s (exact in an fma) tell which of the
+// three neighbours is the rounded root.  This is the IEEE expansion without its input scaling.
+__device__ __forceinline__ float sqrt_rn_safe(float x) {
+  float s = __builtin_amdgcn_sqrtf(x);
+  const float s_dn = u2f(f2u(s) - 1u), s_up = u2f(f2u(s) + 1u);
+  const float t_dn = __builtin_fmaf(-s_dn, s, x);
+  const float t_up = __builtin_fmaf(-s_up, s, x);
+  s = (t_dn <= 0.0f) ? s_dn : s;
+  s = (t_up > 0.0f) ? s_up : s;
+  return s;
+}
+
+// Correctly rounded n/d for n = 0 or 2^-47 <= |n| <= 2^40 and 2^-40 <= d <= 2^40: the IEEE
+// division's expansion (reciprocal estimate, one Newton step, quotient, two exact-residual
+// corrections) without the operand scaling that only extreme exponents need.
+__device__ __forceinline__ float div_rn_safe(float n, float d) {
+  float y = __builtin_amdgcn_rcpf(d);
+  const float e = __builtin_fmaf(-d, y, 1.0f);
+  y = __builtin_fmaf(e, y, y);
+  float q = n * y;
+  float r = __builtin_fmaf(-d, q, n);
+  q = __builtin_fmaf(r, y, q);
+  r = __builtin_fmaf(-d, q, n);
+  return __builtin_fmaf(r, y, q);
+}
+
+// Correctly rounded 1/d for 2^-40 <= d <= 2^40: reciprocal estimate, one Newton step, two
+// exact-residual corrections -- the IEEE division's expansion without the operand scaling that
+// only extreme exponents need.
+__device__ __forceinline__ float rcp_rn_safe(float d) {
+  float y = __builtin_amdgcn_rcpf(d);
+  const float e = __builtin_fmaf(-d, y, 1.0f);
+  y = __builtin_fmaf(e, y, y);
+  float r = __builtin_fmaf(-d, y, 1.0f);
+  const float q = __builtin_fmaf(r, y, y);
+  r = __builtin_fmaf(-d, q, 1.0f);
+  return __builtin_fmaf(r, y, q);
+}
+// 2^-40 <= x <= 2^40, for x >= 0: positive floats order like their bit patterns
+__device__ __forceinline__ bool in_safe_range(float x) { return f2u(x) - 0x2B800000u <= 0x53800000u - 0x2B800000u; }
+
 // ------------------------------------------------------------------ update
 struct UpdateArgs {
   float ibc1, ibc2, eps, lr, decay;
@@ -217,7 +268,7 @@ __device__ __forceinline__ float updated_param(float theta, float mt, float den,
 // mq holds the quantized first moments; theta is replaced by the new parameters.
 template <bool STATS, bool TAIL, bool TABLE, bool FAST>
 __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (&mq)[8], float (&theta)[8],
-                                              uint32_t (&code4)[2], const float (&sn)[2], const float (&inv)[2],
+                                              uint32_t (&code)[8], const float (&sn)[2], const float (&inv)[2],
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
                                               const uint32_t (&den_row)[2], const UpdateArgs& u, uint32_t q, int lane,
                                               uint32_t n_valid, LaneStats& st) {
@@ -226,11 +277,11 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
     const int i = n >> 2;
     const float rho = v[n] * inv[i];
     const uint32_t bits = f2u(rho);
-    const uint32_t idx = min(kVqTop - (bits >> kVqShift), static_cast<uint32_t>(kVqBuckets - 1));
+    const uint32_t idx = __builtin_elementwise_sub_sat(bits >> kVqShift, kVqLow);  // rho <= 1: never past the last bucket
     const uint2 e = VQ[idx];
     uint32_t c = e.y + (bits >= e.x ? 1u : 0u);
     if (TAIL && !is_valid(n, q, lane, n_valid)) c = 0;
-    if ((n & 3) == 0) code4[i] = c; else code4[i] |= c << (8 * (n & 3));
+    code[n] = c;
     if (STATS) {
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
@@ -246,15 +297,23 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
     } else {
       const float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       const float vt = vq * u.ibc2;
-      const float den = __builtin_sqrtf(vt) + u.eps;
-      theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, u);
+      if (FAST) {
+        const float den = sqrt_rn_safe(vt) + u.eps;
+        const float upd = u.lr * div_rn_safe(mt, den);
+        const float dec = theta[n] * u.decay;
+        theta[n] = dec - upd;
+      } else {
+        const float den = __builtin_sqrtf(vt) + u.eps;
+        theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, u);
+      }
     }
   }
 }
 
 // ------------------------------------------------------------------ one quarter tile
-// Lane L = (value vL = L&3, lane group qL = L>>2) owns one (state, row) pair's block scale:
-// state = vL>>1, row = 2q + (vL&1), block within the row = qL >> (lgK-4).
+// Lane L = (value vL = L>>4, lane group qL = L&15) owns one (state, row) pair's block scale:
+// state = vL>>1, row = 2q + (vL&1), block within the row = qL >> (lgK-4).  A block's owners are
+// 4, 8 or 16 neighbouring lanes of one 16-lane row, so their maxima combine by DPP lane swaps.
 template <bool BF16, bool STATS, bool TAIL>
 __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t tile, uint32_t q, uint32_t n_valid,
                                                 const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
@@ -273,7 +332,9 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   STQ_GLOBAL uint32_t* CM = as_global(d.m_codes + static_cast<size_t>(tile) * 64u * bm) + ((q * bm) >> 2) * 64;
   STQ_GLOBAL uint32_t* CV = as_global(d.v_codes + static_cast<size_t>(tile) * 64u * bv) + ((q * bv) >> 2) * 64;
   const size_t sbase = static_cast<size_t>(tile) << (11 - lgK);  // scales per tile = 2048/K
-  const int vL = lane & 3, qL = lane >> 2;
+  // the lane index as a 6-bit unsigned offset: global addresses become uniform base + 32-bit offset
+  const uint32_t ul = static_cast<uint32_t>(lane) & 63u;
+  const int vL = lane >> 4, qL = lane & 15;
   const uint32_t sidx = ((2u * q + static_cast<uint32_t>(vL & 1)) << (8 - lgK)) + (static_cast<uint32_t>(qL) >> (lgK - 4));
   STQ_GLOBAL float* SC = as_global((vL >> 1) ? d.v_scales : d.m_scales);
 
@@ -283,9 +344,9 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   {
     const uint32_t nwm = (s0m + 8u * bm + 31u) >> 5, nwv = (s0v + 8u * bv + 31u) >> 5;  // 1..3 words
 #pragma unroll
-    for (int k = 0; k < 3; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? CM[k * 64 + lane] : 0u;
+    for (int k = 0; k < 3; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? CM[k * 64u + ul] : 0u;
 #pragma unroll
-    for (int k = 0; k < 3; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? CV[k * 64 + lane] : 0u;
+    for (int k = 0; k < 3; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? CV[k * 64u + ul] : 0u;
   }
   float g[8];
   {
@@ -295,11 +356,11 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         if (BF16) {
-          const u32x2 r = reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[lane];
+          const u32x2 r = reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[ul];
           g[4 * i + 0] = u2f(r.x << 16); g[4 * i + 1] = u2f(r.x & 0xFFFF0000u);
           g[4 * i + 2] = u2f(r.y << 16); g[4 * i + 3] = u2f(r.y & 0xFFFF0000u);
         } else {
-          const f32x4 r = reinterpret_cast<STQ_GLOBAL const f32x4*>(G32 + 256 * i)[lane];
+          const f32x4 r = reinterpret_cast<STQ_GLOBAL const f32x4*>(G32 + 256 * i)[ul];
           g[4 * i + 0] = r.x; g[4 * i + 1] = r.y; g[4 * i + 2] = r.z; g[4 * i + 3] = r.w;
         }
       }
@@ -308,7 +369,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       for (int n = 0; n < 8; ++n) {
         float x = 0.0f;
         if (is_valid(n, q, lane, n_valid)) {
-          const int idx = 256 * (n >> 2) + 4 * lane + (n & 3);
+          const uint32_t idx = 256u * (n >> 2) + 4u * ul + (n & 3);
           x = BF16 ? u2f(static_cast<uint32_t>(G16[idx]) << 16) : G32[idx];
         }
         g[n] = x;
@@ -319,10 +380,10 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   // old scales to every lane that needs them: lane j reads the 4 values of its lane group
   float* wsf = reinterpret_cast<float*>(ws);
   float* XR = wsf;                // [4][XS]
-  float* SO = wsf + 4 * XS;       // [64] old scales by owner lane
+  float* SO = wsf + 4 * XS;       // [64] old scales at [lane group * 4 + value]
   float* SN = SO + 64;            // [64] new scales
   float* SI = SN + 64;            // [64] reciprocals of the new scales
-  SO[lane] = sc_old;
+  SO[qL * 4 + vL] = sc_old;
   wave_lds_sync();
   float som[2], sov[2];
   {
@@ -373,12 +434,12 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
-      const f32x4 t = reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[lane];
+      const f32x4 t = reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[ul];
       theta[4 * i] = t.x; theta[4 * i + 1] = t.y; theta[4 * i + 2] = t.z; theta[4 * i + 3] = t.w;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        theta[4 * i + e] = is_valid(4 * i + e, q, lane, n_valid) ? P[256 * i + 4 * lane + e] : 0.0f;
+        theta[4 * i + e] = is_valid(4 * i + e, q, lane, n_valid) ? P[256u * i + 4u * ul + e] : 0.0f;
     }
   }
 
@@ -391,23 +452,30 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     XR[(2 + i) * XS + lane] = pv;
   }
   wave_lds_sync();
+  // the maxima are non-negative, so they order like their bit patterns: integer max, no NaN handling
   float r;
   {
-    const float4 t0 = *reinterpret_cast<const float4*>(XR + vL * XS + qL * 4);
-    r = fmaxf(fmaxf(t0.x, t0.y), fmaxf(t0.z, t0.w));
+    const uint4 t0 = *reinterpret_cast<const uint4*>(XR + vL * XS + qL * 4);
+    uint32_t rb = max(max(t0.x, t0.y), max(t0.z, t0.w));
+    rb = max(rb, dpp_u32<kDppXor1>(rb));
+    rb = max(rb, dpp_u32<kDppXor2>(rb));
+    if (lgK >= 7) rb = max(rb, dpp_u32<kDppHalfMirror>(rb));
+    if (lgK == 8) rb = max(rb, dpp_u32<kDppMirror>(rb));
+    r = u2f(rb);
   }
-  r = fmaxf(r, __shfl_xor(r, 4, 64));
-  r = fmaxf(r, __shfl_xor(r, 8, 64));
-  if (lgK >= 7) r = fmaxf(r, __shfl_xor(r, 16, 64));
-  if (lgK == 8) r = fmaxf(r, __shfl_xor(r, 32, 64));
   if (STATS) {
     if (vL < 2) st.m_max = fmaxf(st.m_max, r); else st.v_max = fmaxf(st.v_max, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
-  const float sc_inv = (sc_new > 0.0f) ? 1.0f / sc_new : 0.0f;
-  SN[lane] = sc_new;
-  SI[lane] = sc_inv;
+  float sc_inv;
+  if (__all(static_cast<int>(sc_new == 0.0f) | static_cast<int>(in_safe_range(sc_new)))) {
+    sc_inv = (sc_new > 0.0f) ? rcp_rn_safe(sc_new) : 0.0f;
+  } else {
+    sc_inv = (sc_new > 0.0f) ? 1.0f / sc_new : 0.0f;
+  }
+  SN[qL * 4 + vL] = sc_new;
+  SI[qL * 4 + vL] = sc_inv;
   if ((static_cast<uint32_t>(qL) & ((1u << (lgK - 4)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
   wave_lds_sync();
 
@@ -419,14 +487,20 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   const bool use_table = n_entries <= kDenEntries;
   const uint32_t l_base = 4u << bv;
   float2* DEN = reinterpret_cast<float2*>(XR);
-  bool fast_div = false;
+  // The short forms of the quotient (and, without a table, of the square root) need every operand
+  // in a range where no intermediate underflows or overflows.  The owner lanes check their scales:
+  // m~ = (s_m*R)*ibc1 is 0 or at least s_m*ibc1/127; v~ = (s_v*L)*ibc2 is 0 or at least
+  // s_v*ibc2*2^-16, so its root lies in [2^-40, 2^39] when s_v*ibc2 lies in [2^-64, 2^78].
+  int bad_bits;
+  if (vL < 2) {
+    bad_bits = (static_cast<int>(sc_new == 0.0f) | static_cast<int>(in_safe_range(sc_new * a.ibc1))) ^ 1;
+  } else {
+    const float x = sc_new * a.ibc2;
+    bad_bits = (static_cast<int>(sc_new == 0.0f) | static_cast<int>(f2u(x) - 0x1F800000u <= 0x66800000u - 0x1F800000u)) ^ 1;
+  }
+  const bool eps_ok = a.eps >= 0x1p-40f && a.eps <= 1.0f;
+  bool fast_div;
   if (use_table) {
-    // the fast quotient needs every operand in a range where no residual underflows or overflows
-    bool bad = false;
-    if (vL < 2) {
-      const float x = sc_new * a.ibc1;
-      bad = !(sc_new == 0.0f || (x >= 0x1p-40f && x <= 0x1p40f));
-    }
     for (uint32_t e = lane; e < n_entries; e += 64) {
       const uint32_t c = e & ((1u << bv) - 1u), rg = e >> bv;
       const uint32_t row = rg >> (8 - lgK), blk = rg & ((1u << (8 - lgK)) - 1u);
@@ -435,11 +509,14 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       const float vt = vq * a.ibc2;
       const float den = __builtin_sqrtf(vt) + a.eps;
       const float rden = 1.0f / den;
-      bad = bad || !(den >= 0x1p-40f && den <= 0x1p40f) || (f2u(den) & 0x7FFFFFu) == 0x7FFFFFu;
+      // (plain integer logic: no short-circuit branches)
+      bad_bits |= (static_cast<int>(in_safe_range(den)) & static_cast<int>((f2u(den) & 0x7FFFFFu) != 0x7FFFFFu)) ^ 1;
       DEN[e] = make_float2(den, rden);
     }
-    fast_div = !__any(bad);
+    fast_div = !__any(bad_bits);
     wave_lds_sync();
+  } else {
+    fast_div = eps_ok && !__any(bad_bits);
   }
 
   // ---- linear symmetric quantization of m; m is replaced by its quantized value ----
@@ -453,18 +530,18 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     const int qmax = (1 << (bm - 1)) - 1;
     const float qmaxf = static_cast<float>(qmax);
     const uint32_t r_base = 4u << bm;
-    uint32_t code4[2];
+    uint32_t code[8];
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int i = n >> 2;
       const float t = (m[n] * inv[i]) * qmaxf;
       // round half to even: adding 1.5*2^23 leaves the integer in the low mantissa bits (|t| <= 127.5)
       const float rr = t + 12582912.0f;
-      int qq = static_cast<int>(f2u(rr)) - (0x4B400000 - qmax);
-      qq = min(max(qq, 0), 2 * qmax);
-      uint32_t u = static_cast<uint32_t>(qq);
+      // |m| <= s and 1/s is within half an ulp, so |t| <= qmax*(1 + 2^-22) rounds to at most qmax:
+      // the clamp of the quantizer's definition can never act and is left out
+      uint32_t u = f2u(rr) - static_cast<uint32_t>(0x4B400000 - qmax);
       if (TAIL && !is_valid(n, q, lane, n_valid)) u = 0;
-      if ((n & 3) == 0) code4[i] = u; else code4[i] |= u << (8 * (n & 3));
+      code[n] = u;
       float mq = sn[i] * lds_at(Rreg, (u << 2) | r_base);
       if (STATS) {
         if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
@@ -475,7 +552,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       }
       m[n] = mq;
     }
-    STQ_SWITCH_BITS(bm, (pack_store<B>(code4, CM, s0m, carry_m, lane)));
+    STQ_SWITCH_BITS(bm, (pack_store<B>(code, CM, s0m, carry_m, ul)));
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
@@ -492,29 +569,51 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
     for (int i = 0; i < 2; ++i)
       den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bv);
-    uint32_t code4[2];
+    uint32_t code[8];
     if (use_table) {
       if (fast_div)
-        quant2_update<STATS, TAIL, true, true>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, true>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
       else
-        quant2_update<STATS, TAIL, true, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
+        quant2_update<STATS, TAIL, true, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
     } else {
-      quant2_update<STATS, TAIL, false, false>(v, m, theta, code4, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
+      if (fast_div)
+        quant2_update<STATS, TAIL, false, true>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
+      else
+        quant2_update<STATS, TAIL, false, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
     }
-    STQ_SWITCH_BITS(bv, (pack_store<B>(code4, CV, s0v, carry_v, lane)));
+    STQ_SWITCH_BITS(bv, (pack_store<B>(code, CV, s0v, carry_v, ul)));
   }
 
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
-      reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[lane] =
+      reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[ul] =
           f32x4{theta[4 * i], theta[4 * i + 1], theta[4 * i + 2], theta[4 * i + 3]};
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (is_valid(4 * i + e, q, lane, n_valid)) P[256 * i + 4 * lane + e] = theta[4 * i + e];
+        if (is_valid(4 * i + e, q, lane, n_valid)) P[256u * i + 4u * ul + e] = theta[4 * i + e];
     }
   }
+}
+
+// The descriptor table is never written while a step runs: reading it through the constant
+// address space gives scalar loads, so everything derived from a descriptor (all base addresses)
+// lives in scalar registers.
+#define STQ_CONSTANT __attribute__((address_space(4)))
+__device__ __forceinline__ TensorDesc load_desc(const TensorDesc* table, uint32_t l) {
+  const STQ_CONSTANT uint64_t* p = (const STQ_CONSTANT uint64_t*)(table + l);
+  static_assert(sizeof(TensorDesc) == 72 || sizeof(TensorDesc) == 80, "descriptor layout");
+  uint64_t w[sizeof(TensorDesc) / 8];
+#pragma unroll
+  for (size_t i = 0; i < sizeof(TensorDesc) / 8; ++i) w[i] = p[i];
+  TensorDesc d;
+  __builtin_memcpy(&d, w, sizeof(TensorDesc));
+  return d;
+}
+__device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uint32_t l) {
+  const STQ_CONSTANT uint32_t* p = (const STQ_CONSTANT uint32_t*)(&table[l].tile_begin);
+  return *p;
 }
 
 // -------------------------------------------------------------- step kernel
@@ -540,14 +639,14 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 4) void step_kerne
   uint32_t lo = 0, hi = a.n_tensors - 1;
   while (lo < hi) {
     const uint32_t mid = (lo + hi + 1) >> 1;
-    if (a.desc[mid].tile_begin <= t) lo = mid; else hi = mid - 1;
+    if (desc_tile_begin(a.desc, mid) <= t) lo = mid; else hi = mid - 1;
   }
   uint32_t l = __builtin_amdgcn_readfirstlane(lo);
 
   LaneStats st;
   if (STATS) st.clear_all();
   while (t < t_end) {
-    const TensorDesc d = a.desc[l];
+    const TensorDesc d = load_desc(a.desc, l);
     const uint32_t stop = min(t_end, d.tile_begin + d.n_tiles);
     for (; t < stop; ++t) {
       const uint32_t tile = t - d.tile_begin;

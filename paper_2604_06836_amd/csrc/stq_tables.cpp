@@ -33,9 +33,9 @@ bool build_table_image(std::vector<uint32_t>& img) {
     for (int k = 0; k < kmax; ++k) tb[k] = f2u(table_T(b, k));
     uint32_t* vq = &img[kTabVqOff + (b - 2) * kVqBuckets * 2];
     for (int idx = 0; idx < kVqBuckets; ++idx) {
-      const bool last = idx == kVqBuckets - 1;
-      const uint64_t lo = last ? 0 : (static_cast<uint64_t>(kVqTop - idx) << kVqShift);
-      const uint64_t hi = idx == 0 ? (1ull << 32) : (static_cast<uint64_t>(kVqTop - idx + 1) << kVqShift);
+      const bool last = idx == 0;  // the catch-all bucket below the lowest threshold
+      const uint64_t lo = last ? 0 : (static_cast<uint64_t>(kVqLow + idx) << kVqShift);
+      const uint64_t hi = idx == kVqBuckets - 1 ? (1ull << 32) : (static_cast<uint64_t>(kVqLow + idx + 1) << kVqShift);
       uint32_t base = 0, thr = 0xFFFFFFFFu;
       int inside = 0;
       for (int k = 0; k < kmax; ++k) {

@@ -12,12 +12,13 @@ constexpr int kMinBits = 2;
 constexpr int kMaxBits = 8;
 
 // Second-moment quantizer as a bucketed search over the bit pattern of
-// rho = v / blockmax in (0, 1]:  bucket = min(kVqTop - (bits(rho) >> kVqShift), kVqBuckets-1),
-// code = entry.base + (bits(rho) >= entry.thr).  Bucket width 2^18 ulps keeps at most one
-// threshold per bucket for every width up to 8 bits.
+// rho = v / blockmax in (0, 1]:  bucket = max((bits(rho) >> kVqShift) - kVqLow, 0)  (one saturating
+// subtraction), code = entry.base + (bits(rho) >= entry.thr).  Bucket width 2^18 ulps keeps at most
+// one threshold per bucket for every width up to 8 bits.
 constexpr int kVqShift = 18;
-constexpr uint32_t kVqTop = 0x3F800000u >> kVqShift;  // bucket 0 holds rho >= 1
-constexpr int kVqBuckets = 514;                       // 16 octaves x 32 + bucket 0 + everything below
+constexpr uint32_t kVqTop = 0x3F800000u >> kVqShift;  // the last bucket holds rho >= 1
+constexpr int kVqBuckets = 514;                       // everything below + 16 octaves x 32 + the last
+constexpr uint32_t kVqLow = kVqTop - (kVqBuckets - 1);
 struct VqEntry { uint32_t thr; uint32_t base; };
 
 // Offsets (in 32-bit words) inside the table image that stq_init uploads and every
