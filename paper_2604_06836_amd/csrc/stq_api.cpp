@@ -23,6 +23,7 @@ struct stq_ctx {
   uint32_t max_tensors = 0;
   uint32_t n_cu = 0;
   uint32_t groups_per_cu = 2;
+  uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
   uint32_t* d_tables = nullptr;
   TensorDesc* d_desc = nullptr;
   double* d_stats = nullptr;
@@ -157,6 +158,10 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 8) c->groups_per_cu = static_cast<uint32_t>(v);
   }
+  if (const char* e = std::getenv("STQ_CHUNK")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 1 && v <= (1 << 20)) c->chunk_override = static_cast<uint32_t>(v);
+  }
   DeviceGuard g(device);
   bool ok = g.ok;
   ok = ok && hipMalloc(&c->d_tables, img.size() * 4) == hipSuccess;
@@ -257,6 +262,12 @@ int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits
   const uint32_t max_groups = ctx->n_cu * ctx->groups_per_cu;
   const uint32_t need_groups = (total + kWavesPerGroup - 1) / kWavesPerGroup;
   const uint32_t groups = need_groups < max_groups ? need_groups : max_groups;
+  // tile order (see step_kernel): one contiguous range per wave when statistics are collected,
+  // else interleaved chunks -- single tiles, or four at a time once a wave has many of them
+  const uint64_t n_waves = static_cast<uint64_t>(groups) * kWavesPerGroup;
+  const uint64_t per_wave = (total + n_waves - 1) / n_waves;
+  a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
+  if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
   if (launch_step(a, hp->grad_dtype == 1, want_stats, groups, stream) != 0) return STQ_EHIP;
   if (want_stats)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
