@@ -356,11 +356,11 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         if (BF16) {
-          const u32x2 r = reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[ul];
+          const u32x2 r = __builtin_nontemporal_load(&reinterpret_cast<STQ_GLOBAL const u32x2*>(G16 + 256 * i)[ul]);
           g[4 * i + 0] = u2f(r.x << 16); g[4 * i + 1] = u2f(r.x & 0xFFFF0000u);
           g[4 * i + 2] = u2f(r.y << 16); g[4 * i + 3] = u2f(r.y & 0xFFFF0000u);
         } else {
-          const f32x4 r = reinterpret_cast<STQ_GLOBAL const f32x4*>(G32 + 256 * i)[ul];
+          const f32x4 r = __builtin_nontemporal_load(&reinterpret_cast<STQ_GLOBAL const f32x4*>(G32 + 256 * i)[ul]);
           g[4 * i + 0] = r.x; g[4 * i + 1] = r.y; g[4 * i + 2] = r.z; g[4 * i + 3] = r.w;
         }
       }
@@ -430,11 +430,14 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   }
 
   // ---- parameters: issued here so that they arrive while the block maxima are reduced ----
+  // Parameters and gradients are touched once per step: non-temporal accesses keep them from
+  // displacing the code and scale lines in the caches (measured: both the load and the store of
+  // the parameters must carry the hint; on the code and scale streams it loses).
   float theta[8];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
-      const f32x4 t = reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[ul];
+      const f32x4 t = __builtin_nontemporal_load(&reinterpret_cast<STQ_GLOBAL const f32x4*>(P + 256 * i)[ul]);
       theta[4 * i] = t.x; theta[4 * i + 1] = t.y; theta[4 * i + 2] = t.z; theta[4 * i + 3] = t.w;
     } else {
 #pragma unroll
@@ -587,8 +590,8 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (!TAIL) {
-      reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[ul] =
-          f32x4{theta[4 * i], theta[4 * i + 1], theta[4 * i + 2], theta[4 * i + 3]};
+      __builtin_nontemporal_store(f32x4{theta[4 * i], theta[4 * i + 1], theta[4 * i + 2], theta[4 * i + 3]},
+                                  &reinterpret_cast<STQ_GLOBAL f32x4*>(P + 256 * i)[ul]);
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
