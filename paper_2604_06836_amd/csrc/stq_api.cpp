@@ -22,7 +22,7 @@ struct stq_ctx {
   int device = -1;
   uint32_t max_tensors = 0;
   uint32_t n_cu = 0;
-  uint32_t groups_per_cu = 2;
+  uint32_t groups_per_cu = 3;    // resident workgroups per CU the plain step kernel is launched for
   uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
   uint32_t* d_tables = nullptr;
   TensorDesc* d_desc = nullptr;
@@ -259,12 +259,15 @@ int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits
   a.lgK = static_cast<uint32_t>(lg_block(hp->block));
 
   const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
-  const uint32_t max_groups = ctx->n_cu * ctx->groups_per_cu;
-  const uint32_t need_groups = (total + kWavesPerGroup - 1) / kWavesPerGroup;
+  // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
+  const uint32_t per_cu = want_stats ? (ctx->groups_per_cu < 2 ? ctx->groups_per_cu : 2) : ctx->groups_per_cu;
+  const uint32_t max_groups = ctx->n_cu * per_cu;
+  const uint32_t wpg = kWavesPerGroup;
+  const uint32_t need_groups = (total + wpg - 1) / wpg;
   const uint32_t groups = need_groups < max_groups ? need_groups : max_groups;
   // tile order (see step_kernel): one contiguous range per wave when statistics are collected,
   // else interleaved chunks -- single tiles, or four at a time once a wave has many of them
-  const uint64_t n_waves = static_cast<uint64_t>(groups) * kWavesPerGroup;
+  const uint64_t n_waves = static_cast<uint64_t>(groups) * wpg;
   const uint64_t per_wave = (total + n_waves - 1) / n_waves;
   a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;

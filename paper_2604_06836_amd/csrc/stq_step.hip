@@ -7,7 +7,7 @@
 // -ffp-contract=off); division and square root are the correctly rounded ones.
 //
 // Work decomposition: one wavefront owns one 2048-element tile at a time and processes it as four
-// quarters of 2 rows: a quarter's working set fits the 128 registers of four waves per SIMD with
+// quarters of 2 rows: a quarter's working set fits the 80 registers of six waves per SIMD with
 // nothing spilled to scratch memory, so the kernel's HBM traffic is the algorithmic traffic.
 // In row i lane j holds the 4 elements 256*i + 4*j + e, so
 // every parameter and gradient access is a coalesced 16-byte (8-byte for bf16) per-lane access,
@@ -625,18 +625,20 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // neighbouring addresses, which the memory system serves best.  The statistics variant flushes
 // its sums once per tensor a wave has touched, so the host gives it one chunk per wave (a
 // contiguous range: few tensors per wave).
-// The statistics variant needs about 70 more registers and runs at a lower occupancy.
+// The statistics variant needs about 80 more registers and runs one workgroup per CU at a time
+// (a second workgroup of six waves per CU measured slower).
 template <bool BF16, bool STATS>
-__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 4) void step_kernel(const StepArgs a) {
+__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kernel(const StepArgs a) {
+  constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
-  for (int i = threadIdx.x; i < kTabWords; i += 64 * kWavesPerGroup) lds[i] = a.tables[i];
+  for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
   __syncthreads();
 
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* ws = lds + kTabWords + wave * kWaveScratch;
-  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * kWavesPerGroup;
-  const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * kWavesPerGroup + wave;
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * kWaves;
+  const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
   const uint64_t C = a.chunk;
   uint64_t base = gw * C;
   if (base >= a.total_tiles) return;
