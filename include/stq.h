@@ -145,6 +145,22 @@ int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state,
                const void* src_codes, uint32_t src_bits,
                void* dst_codes, uint32_t dst_bits, void* hip_stream);
 
+/* One width change of one state, for stq_repack_many: the arguments of stq_repack. */
+typedef struct {
+  uint64_t numel;
+  const void* src_codes; /* device, 256-byte aligned */
+  void* dst_codes;       /* device, 256-byte aligned, must not overlap src_codes */
+  uint8_t state;         /* 0 = first moment, 1 = second moment */
+  uint8_t src_bits, dst_bits;
+} stq_repack_job;
+
+/* n width changes (as stq_repack, one per job) in ONE kernel launch: what Map's new
+ * plan asks for after a decision, when many layers change at once.  jobs is a host
+ * array, read before the call returns; n may not exceed twice the context's
+ * max_tensors.  Jobs must not overlap each other's destinations. */
+int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32_t block,
+                    void* hip_stream);
+
 /* Host-side bit-width decision for n layers (Algorithm 1, the "if t mod U = 0
  * or t < 5" body; Eq. 2, 3, 4, 7, 8; Section 3.4 score and Map): updates *ema and
  * writes plan_out[l].  score_out (host, n doubles) may be NULL.  Linear in n. */

@@ -58,8 +58,13 @@ class DecideCfg(C.Structure):
                 ("thr", C.POINTER(C.c_double)), ("bits", C.POINTER(C.c_uint8))]
 
 
+class RepackJob(C.Structure):
+    _fields_ = [("numel", C.c_uint64), ("src_codes", C.c_void_p), ("dst_codes", C.c_void_p),
+                ("state", C.c_uint8), ("src_bits", C.c_uint8), ("dst_bits", C.c_uint8)]
+
+
 EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_stats",
-           "stq_repack", "stq_decide", "stq_table", "stq_strerror"]
+           "stq_repack", "stq_repack_many", "stq_decide", "stq_table", "stq_strerror"]
 
 _lib = None
 
@@ -84,6 +89,7 @@ def load_library():
     L.stq_step.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(HParams), vp]
     L.stq_stats.argtypes = [vp, C.POINTER(LayerStats), u32, vp]
     L.stq_repack.argtypes = [vp, u64, u32, C.c_int, vp, u32, vp, u32, vp]
+    L.stq_repack_many.argtypes = [vp, C.POINTER(RepackJob), u32, u32, vp]
     L.stq_decide.argtypes = [C.POINTER(DecideState), C.POINTER(LayerStats), u32, C.POINTER(DecideCfg), u32,
                              C.POINTER(Bits), C.POINTER(C.c_double)]
     L.stq_table.argtypes = [C.c_int, u32, C.POINTER(C.c_float), u32]
@@ -189,6 +195,13 @@ class Context:
         out = (LayerStats * n)()
         _check(self._lib.stq_stats(self._h, out, n, C.c_void_p(stream)), "stq_stats")
         return out
+
+    def repack_many(self, jobs, block: int, stream: int = 0):
+        """jobs: sequence of (numel, state, src_ptr, src_bits, dst_ptr, dst_bits)."""
+        arr = (RepackJob * len(jobs))()
+        for i, (numel, state, src, sb, dst, db) in enumerate(jobs):
+            arr[i] = RepackJob(numel, src, dst, state, sb, db)
+        _check(self._lib.stq_repack_many(self._h, arr, len(jobs), block, C.c_void_p(stream)), "stq_repack_many")
 
     def repack(self, numel: int, block: int, state: int, src: int, src_bits: int, dst: int, dst_bits: int,
                stream: int = 0):

@@ -30,6 +30,11 @@ struct stq_ctx {
   TensorDesc* h_stage[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
   hipEvent_t stage_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
   int ring_pos = 0;
+  uint32_t* d_luts = nullptr;                // every conversion table of the re-pack, kRepackLuts x 256 words
+  RepackJob* d_jobs = nullptr;               // 2 * max_tensors
+  RepackJob* h_jobs[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
+  hipEvent_t jobs_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  int jobs_pos = 0;
   double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
   std::vector<TensorDesc> uploaded;          // what d_desc currently holds
   std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
@@ -173,6 +178,23 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
     ok = ok && hipEventCreateWithFlags(&c->stage_done[k], hipEventDisableTiming) == hipSuccess;
   }
   ok = ok && hipMemcpy(c->d_tables, img.data(), img.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+  // every conversion table of the re-pack: (state, old width, new width) -> 256 codes, one word each
+  std::vector<uint32_t> luts(static_cast<size_t>(kRepackLuts) * 256);
+  for (int st = 0; st < 2; ++st)
+    for (int bo = kMinBits; bo <= kMaxBits; ++bo)
+      for (int bn = kMinBits; bn <= kMaxBits; ++bn) {
+        uint8_t one[256];
+        build_repack_lut(st, bo, bn, one);
+        uint32_t* dst = &luts[static_cast<size_t>(repack_lut_index(st, bo, bn)) * 256];
+        for (int i = 0; i < 256; ++i) dst[i] = one[i];
+      }
+  ok = ok && hipMalloc(&c->d_luts, luts.size() * 4) == hipSuccess;
+  ok = ok && hipMemcpy(c->d_luts, luts.data(), luts.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_jobs, sizeof(RepackJob) * 2 * max_tensors) == hipSuccess;
+  for (int k = 0; k < kRing && ok; ++k) {
+    ok = ok && hipHostMalloc(&c->h_jobs[k], sizeof(RepackJob) * 2 * max_tensors, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->jobs_done[k], hipEventDisableTiming) == hipSuccess;
+  }
   ok = ok && hipMemset(c->d_stats, 0, sizeof(double) * kStatSlots * max_tensors) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) { stq_destroy(c); return STQ_EHIP; }
@@ -189,6 +211,12 @@ int stq_destroy(stq_ctx* c) {
   if (c->d_desc) (void)hipFree(c->d_desc);
   if (c->d_stats) (void)hipFree(c->d_stats);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
+  if (c->d_luts) (void)hipFree(c->d_luts);
+  if (c->d_jobs) (void)hipFree(c->d_jobs);
+  for (int k = 0; k < kRing; ++k) {
+    if (c->h_jobs[k]) (void)hipHostFree(c->h_jobs[k]);
+    if (c->jobs_done[k]) (void)hipEventDestroy(c->jobs_done[k]);
+  }
   for (int k = 0; k < kRing; ++k) {
     if (c->h_stage[k]) (void)hipHostFree(c->h_stage[k]);
     if (c->stage_done[k]) (void)hipEventDestroy(c->stage_done[k]);
@@ -328,6 +356,54 @@ int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state, const vo
   a.b_new = dst_bits;
   build_repack_lut(state, static_cast<int>(src_bits), static_cast<int>(dst_bits), a.lut);
   return launch_repack(a, stream) == 0 ? STQ_OK : STQ_EHIP;
+}
+
+int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32_t block, void* stream) {
+  if (!ctx || !jobs || n == 0 || n > 2 * ctx->max_tensors) return STQ_EINVAL;
+  if (lg_block(block) < 0) return STQ_EBLOCK;
+  std::vector<RepackJob> table(n);
+  uint64_t total = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    const stq_repack_job& j = jobs[i];
+    if (!j.src_codes || !j.dst_codes || j.numel == 0 || j.state > 1) return STQ_EINVAL;
+    if (int e = check_bits(j.src_bits)) return e;
+    if (int e = check_bits(j.dst_bits)) return e;
+    if (!aligned(j.src_codes, 256) || !aligned(j.dst_codes, 256)) return STQ_EALIGN;
+    const uint64_t tiles = (j.numel + kTile - 1) / kTile;
+    if (total + tiles > 0xFFFFFFFFull) return STQ_EINVAL;
+    const uintptr_t s0 = reinterpret_cast<uintptr_t>(j.src_codes), s1 = s0 + tiles * 256 * j.src_bits;
+    const uintptr_t d0 = reinterpret_cast<uintptr_t>(j.dst_codes), d1 = d0 + tiles * 256 * j.dst_bits;
+    if (s0 < d1 && d0 < s1) return STQ_EINVAL;
+    RepackJob& r = table[i];
+    r.src = static_cast<const uint32_t*>(j.src_codes);
+    r.dst = static_cast<uint32_t*>(j.dst_codes);
+    r.numel = j.numel;
+    r.tile_begin = static_cast<uint32_t>(total);
+    r.n_tiles = static_cast<uint32_t>(tiles);
+    r.b_old = j.src_bits;
+    r.b_new = j.dst_bits;
+    r.lut = repack_lut_index(j.state, j.src_bits, j.dst_bits);
+    r.pad = 0;
+    total += tiles;
+  }
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int k = ctx->jobs_pos;
+  ctx->jobs_pos = (k + 1) % kRing;
+  if (hipEventSynchronize(ctx->jobs_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
+  std::memcpy(ctx->h_jobs[k], table.data(), sizeof(RepackJob) * n);
+  if (hipMemcpyAsync(ctx->d_jobs, ctx->h_jobs[k], sizeof(RepackJob) * n, hipMemcpyHostToDevice, s) != hipSuccess)
+    return STQ_EHIP;
+  if (hipEventRecord(ctx->jobs_done[k], s) != hipSuccess) return STQ_EHIP;
+  RepackManyArgs a;
+  a.jobs = ctx->d_jobs;
+  a.n_jobs = n;
+  a.total_tiles = static_cast<uint32_t>(total);
+  a.luts = ctx->d_luts;
+  const uint64_t need = (total + 3) / 4;
+  const uint64_t cap = static_cast<uint64_t>(ctx->n_cu) * 8;
+  return launch_repack_many(a, static_cast<uint32_t>(need < cap ? need : cap), stream) == 0 ? STQ_OK : STQ_EHIP;
 }
 
 }  // extern "C"

@@ -55,10 +55,30 @@ struct RepackArgs {
   uint8_t lut[256];
 };
 
+// One width change inside a batched re-pack launch.
+struct RepackJob {
+  const uint32_t* src; uint32_t* dst;
+  uint64_t numel;
+  uint32_t tile_begin, n_tiles;  // position in the launch-wide tile order
+  uint32_t b_old, b_new;
+  uint32_t lut;                  // index of the conversion table, see repack_lut_index
+  uint32_t pad;
+};
+constexpr uint32_t kRepackLuts = 2 * 7 * 7;  // (state, old width, new width)
+constexpr uint32_t repack_lut_index(uint32_t state, uint32_t b_old, uint32_t b_new) {
+  return (state * 7 + (b_old - 2)) * 7 + (b_new - 2);
+}
+struct RepackManyArgs {
+  const RepackJob* jobs;
+  uint32_t n_jobs, total_tiles;
+  const uint32_t* luts;  // [kRepackLuts][256] words
+};
+
 // Launchers implemented in stq_step.hip and stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
 int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream);
 int launch_zero(const ZeroArgs& a, void* stream);
 int launch_repack(const RepackArgs& a, void* stream);
+int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream);
 int launch_fill_zero(uint32_t* p, uint64_t words, void* stream);
 
 }  // namespace stq

@@ -156,6 +156,43 @@ def test_repack_every_width_pair(oracle, ctx, state):
             assert np.array_equal(dst.cpu().numpy().view(np.uint32), want), (state, b_old, b_new)
 
 
+def test_repack_many_matches_oracle(oracle, ctx):
+    # 40 width changes of both states in one launch: sizes from 1 element to several tiles, ragged
+    # tails, every old/new width; destinations pre-filled so that unwritten words would show
+    rng = np.random.default_rng(77)
+    sizes = [1, 63, 2047, 2048, 2049, 5 * 2048 + 700, 12 * 2048, 3 * 2048 + 1]
+    jobs, keep = [], []
+    for i in range(40):
+        n = sizes[i % len(sizes)] + (i // len(sizes)) * 17
+        state = i % 2
+        b_old = int(rng.integers(2, 9))
+        b_new = int(rng.choice([b for b in range(2, 9) if b != b_old]))
+        hi = 2 ** b_old - (1 if state == 0 else 0)
+        codes = rng.integers(0, hi, n, dtype=np.uint8)
+        src = torch.from_numpy(oracle.pack(codes, b_old).view(np.int32)).cuda()
+        cb, _ = stq.state_bytes(n, 128, b_new)
+        dst = torch.full((cb // 4,), -1, dtype=torch.int32, device="cuda")
+        jobs.append((n, state, src.data_ptr(), b_old, dst.data_ptr(), b_new))
+        keep.append((codes, src, dst, state, b_old, b_new))
+    ctx.repack_many(jobs, 128, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i, (codes, src, dst, state, b_old, b_new) in enumerate(keep):
+        want = oracle.pack(oracle.repack(codes, state, b_old, b_new), b_new)
+        assert np.array_equal(dst.cpu().numpy().view(np.uint32), want), (i, state, b_old, b_new)
+    # rejected arguments
+    lib = stq.load_library()
+    n, state, src, b0, dst, b1 = jobs[5]
+    def call(j, count=1):
+        arr = (binding.RepackJob * 1)(binding.RepackJob(j[0], j[2], j[4], j[1], j[3], j[5]))
+        return lib.stq_repack_many(ctx._h, arr, count, 128, None)
+    assert call((n, state, src, 9, dst, b1)) == -3
+    assert call((n, state, src, b0, dst + 4, b1)) == -2
+    assert call((n, state, src, b0, src, b1)) == -1      # overlapping source and destination
+    assert call((0, state, src, b0, dst, b1)) == -1
+    assert call((n, 2, src, b0, dst, b1)) == -1
+    assert call((n, state, src, b0, dst, b1), count=0) == -1
+
+
 def test_transitions_config3_scaled(oracle, ctx):
     # ViT-shaped tensors (reduced), Student-t gradients, K = 256, widths switching every 5 steps
     w = configs.scaled(configs.get_workload("vit-b16"), 40_000, 12)

@@ -68,24 +68,27 @@ class DeviceModel:
     def step(self, t: int, stats: bool = False):
         self.ctx.step(self.tensors, self.cplan, hparams(self.w, t, stats), self.stream)
 
-    def apply_plan(self, new_plan: Sequence[Tuple[int, int]]) -> int:
+    def apply_plan(self, new_plan: Sequence[Tuple[int, int]], batched: bool = True) -> int:
         """Re-pack every state whose width changed (out of place) and adopt the new plan.
         Returns the number of re-packed states."""
-        changed = 0
+        jobs, fresh = [], []
         for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
             n = self.param[l].numel()
-            if bm0 != bm1:
-                cb, _ = stq.state_bytes(n, self.w.K, bm1)
+            for state, old, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
+                if b0 == b1:
+                    continue
+                cb, _ = stq.state_bytes(n, self.w.K, b1)
                 dst = torch.empty(cb // 4, dtype=torch.int32, device=self.device)
-                self.ctx.repack(n, self.w.K, 0, self.m_codes[l].data_ptr(), bm0, dst.data_ptr(), bm1, self.stream)
-                self.m_codes[l] = dst
-                changed += 1
-            if bv0 != bv1:
-                cb, _ = stq.state_bytes(n, self.w.K, bv1)
-                dst = torch.empty(cb // 4, dtype=torch.int32, device=self.device)
-                self.ctx.repack(n, self.w.K, 1, self.v_codes[l].data_ptr(), bv0, dst.data_ptr(), bv1, self.stream)
-                self.v_codes[l] = dst
-                changed += 1
+                jobs.append((n, state, old[l].data_ptr(), b0, dst.data_ptr(), b1))
+                fresh.append((old, l, dst))
+        changed = len(jobs)
+        if batched and jobs:
+            self.ctx.repack_many(jobs, self.w.K, self.stream)
+        else:
+            for n, state, src, b0, dst, b1 in jobs:
+                self.ctx.repack(n, self.w.K, state, src, b0, dst, b1, self.stream)
+        for old, l, dst in fresh:   # the old buffers stay alive until the launches above are queued
+            old[l] = dst
         self.plan = [tuple(p) for p in new_plan]
         self._rebuild()
         return changed
