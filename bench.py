@@ -127,11 +127,9 @@ def main():
         if w.transitions == "switch10pct_every5":
             new_plan = w.switch_plan(plan, t)
             if new_plan != plan:
-                repacked += dm.apply_plan(new_plan)
+                dm.tensors = tensor_sets[k]
+                repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
                 plan = new_plan
-                for kk in (0, 1):
-                    dm.grad = grads[kk]; dm._rebuild(); tensor_sets[kk] = dm.tensors
-                dm.grad = grads[k]
         dm.tensors = tensor_sets[k]
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
@@ -145,10 +143,8 @@ def main():
                 _, sc = stq.decide(binding.DecideState(0, 0, 0), st, t, alpha=0.3, tau=4.0, thr=(), bits=(4,))
                 ladder = calibrate_ladder(sc, w.p_m)
             new_plan, _ = stq.decide(ema, st, t, alpha=0.3, tau=4.0, v_offset=-0.5, thr=ladder, bits=w.bits_m)
-            repacked += dm.apply_plan(new_plan)
+            repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
             plan = new_plan
-            for kk in (0, 1):
-                dm.grad = grads[kk]; dm._rebuild(); tensor_sets[kk] = dm.tensors
 
     t = 0
     for _ in range(args.warmup):

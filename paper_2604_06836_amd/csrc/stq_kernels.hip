@@ -77,57 +77,112 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
   }
 }
 
-// Many width changes in one launch.  Wave w of W takes tiles w, w+W, ... of the launch-wide tile
-// order; when it enters another job it reloads that job's conversion table into its LDS slice.
+// The lane's 32 codes of width B out of / into its B stream words; all shifts are compile-time.
+template <int B>
+__device__ __forceinline__ void unpack32(const uint32_t* src, uint32_t (&code)[32]) {
+  uint32_t w[B];
+#pragma unroll
+  for (int p = 0; p < B; ++p) w[p] = src[64 * p];
+  constexpr uint32_t mask = (1u << B) - 1u;
+#pragma unroll
+  for (int n = 0; n < 32; ++n) {
+    const int off = n * B, p = off >> 5, sh = off & 31;
+    if (sh + B <= 32) code[n] = (w[p] >> sh) & mask;
+    else code[n] = ((w[p] >> sh) | (w[p + 1] << (32 - sh))) & mask;
+  }
+}
+
+template <int B>
+__device__ __forceinline__ void pack32(const uint32_t (&code)[32], uint32_t* dst) {
+  uint32_t w[B];
+#pragma unroll
+  for (int p = 0; p < B; ++p) w[p] = 0u;
+#pragma unroll
+  for (int n = 0; n < 32; ++n) {
+    const int off = n * B, p = off >> 5, sh = off & 31;
+    w[p] |= code[n] << sh;
+    if (sh + B > 32) w[p + 1] |= code[n] >> (32 - sh);
+  }
+#pragma unroll
+  for (int p = 0; p < B; ++p) dst[64 * p] = w[p];
+}
+
+#define STQ_SWITCH_WIDTH(bits, CALL)       \
+  switch (bits) {                          \
+    case 2: { constexpr int B = 2; CALL; } break; \
+    case 3: { constexpr int B = 3; CALL; } break; \
+    case 4: { constexpr int B = 4; CALL; } break; \
+    case 5: { constexpr int B = 5; CALL; } break; \
+    case 6: { constexpr int B = 6; CALL; } break; \
+    case 7: { constexpr int B = 7; CALL; } break; \
+    default: { constexpr int B = 8; CALL; } break; \
+  }
+
+// The job table is not written while the kernel runs: reading it through the constant address
+// space gives scalar loads.
+#define STQ_CONSTANT __attribute__((address_space(4)))
+__device__ __forceinline__ RepackJob load_job(const RepackJob* table, uint32_t j) {
+  const STQ_CONSTANT uint64_t* p = (const STQ_CONSTANT uint64_t*)(table + j);
+  static_assert(sizeof(RepackJob) == 48, "job layout");
+  uint64_t w[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) w[i] = p[i];
+  RepackJob r;
+  __builtin_memcpy(&r, w, sizeof(RepackJob));
+  return r;
+}
+__device__ __forceinline__ uint32_t job_tile_begin(const RepackJob* table, uint32_t j) {
+  return *(const STQ_CONSTANT uint32_t*)(&table[j].tile_begin);
+}
+
+// Many width changes in one launch.  Wave w of W takes the chunks w, w+W, ... of kRepackChunk
+// consecutive tiles of the launch-wide tile order; when it enters a job with another conversion
+// table it reloads its LDS slice.
+constexpr uint32_t kRepackChunk = 8;
 __global__ __launch_bounds__(256) void repack_many_kernel(const RepackManyArgs a) {
   __shared__ uint32_t lut_all[4][256];
-  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* lut = lut_all[wave];
-  const uint32_t n_waves = gridDim.x * 4;
-  uint32_t t = blockIdx.x * 4 + wave;
-  if (t >= a.total_tiles) return;
-  // job holding tile t: last j with tile_begin <= t
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * 4;
+  uint64_t base = (static_cast<uint64_t>(blockIdx.x) * 4 + wave) * kRepackChunk;
+  if (base >= a.total_tiles) return;
+  // job holding the first tile: last j with tile_begin <= base
   uint32_t lo = 0, hi = a.n_jobs - 1;
   while (lo < hi) {
     const uint32_t mid = (lo + hi + 1) >> 1;
-    if (a.jobs[mid].tile_begin <= t) lo = mid; else hi = mid - 1;
+    if (job_tile_begin(a.jobs, mid) <= static_cast<uint32_t>(base)) lo = mid; else hi = mid - 1;
   }
   uint32_t j = lo, loaded = 0xFFFFFFFFu;
-  for (; t < a.total_tiles; t += n_waves) {
-    while (t >= a.jobs[j].tile_begin + a.jobs[j].n_tiles) ++j;  // t < total_tiles: a later job holds it
-    const RepackJob job = a.jobs[j];
-    if (loaded != job.lut) {
+  RepackJob job = load_job(a.jobs, j);
+  for (; base < a.total_tiles; base += n_waves * kRepackChunk) {
+   const uint32_t c_end = static_cast<uint32_t>(min(base + kRepackChunk, static_cast<uint64_t>(a.total_tiles)));
+   for (uint32_t t = static_cast<uint32_t>(base); t < c_end; ++t) {
+    while (t >= job.tile_begin + job.n_tiles) job = load_job(a.jobs, ++j);  // t < total_tiles: a later job holds it
+    const uint32_t b_old = job.b_old, b_new = job.b_new, which = job.lut;
+    if (loaded != which) {
       __builtin_amdgcn_wave_barrier();  // the previous tile's table reads are done (same wave, in order)
-      for (uint32_t k = lane; k < 256; k += 64) lut[k] = a.luts[job.lut * 256 + k];
+      for (uint32_t k = lane; k < 256; k += 64) lut[k] = a.luts[which * 256 + k];
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      loaded = job.lut;
+      loaded = which;
     }
     const uint64_t tile = t - job.tile_begin;
-    const uint32_t* src = job.src + tile * 64 * job.b_old + lane;
-    uint32_t* dst = job.dst + tile * 64 * job.b_new + lane;
-    const uint32_t mask = (1u << job.b_old) - 1u;
-    uint64_t in = 0, out = 0;
-    uint32_t in_bits = 0, out_bits = 0, ip = 0, op = 0;
-    for (uint32_t n = 0; n < 32; ++n) {
-      if (in_bits < job.b_old) {
-        in |= static_cast<uint64_t>(src[64 * ip++]) << in_bits;
-        in_bits += 32;
-      }
-      const uint32_t code = static_cast<uint32_t>(in) & mask;
-      in >>= job.b_old;
-      in_bits -= job.b_old;
-      const uint64_t idx = tile * kTile + 256 * (n >> 2) + 4 * lane + (n & 3);
-      const uint32_t c2 = idx < job.numel ? lut[code] : 0u;
-      out |= static_cast<uint64_t>(c2) << out_bits;
-      out_bits += job.b_new;
-      if (out_bits >= 32) {
-        dst[64 * op++] = static_cast<uint32_t>(out);
-        out >>= 32;
-        out_bits -= 32;
-      }
+    const uint32_t* src = job.src + tile * 64 * b_old + lane;
+    uint32_t* dst = job.dst + tile * 64 * b_new + lane;
+    uint32_t code[32];
+    STQ_SWITCH_WIDTH(b_old, (unpack32<B>(src, code)));
+#pragma unroll
+    for (int n = 0; n < 32; ++n) code[n] = lut[code[n]];
+    const uint64_t left = job.numel - tile * kTile;
+    if (left < static_cast<uint64_t>(kTile)) {  // ragged last tile: pad codes are 0
+      const uint32_t n_valid = static_cast<uint32_t>(left);
+#pragma unroll
+      for (int n = 0; n < 32; ++n)
+        if (256u * (n >> 2) + 4u * lane + (n & 3) >= n_valid) code[n] = 0u;
     }
+    STQ_SWITCH_WIDTH(b_new, (pack32<B>(code, dst)));
+   }
   }
 }
 

@@ -33,6 +33,7 @@ class DeviceModel:
         self.v_codes: List[torch.Tensor] = []
         self.m_scales: List[torch.Tensor] = []
         self.v_scales: List[torch.Tensor] = []
+        self._spare, self._base = {}, {}   # (tensor, state) -> spare buffer / allocation behind the current view
         gdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
         for l, (_, n) in enumerate(w.tensors):
             bm, bv = self.plan[l]
@@ -68,29 +69,44 @@ class DeviceModel:
     def step(self, t: int, stats: bool = False):
         self.ctx.step(self.tensors, self.cplan, hparams(self.w, t, stats), self.stream)
 
-    def apply_plan(self, new_plan: Sequence[Tuple[int, int]], batched: bool = True) -> int:
+    def apply_plan(self, new_plan: Sequence[Tuple[int, int]], batched: bool = True, also_patch=()) -> int:
         """Re-pack every state whose width changed (out of place) and adopt the new plan.
-        Returns the number of re-packed states."""
+        Returns the number of re-packed states.  Destination buffers come from a per-state spare
+        (the buffer the state used before, kept at the size of the widest code) so that a loop of
+        transitions allocates nothing once warm.  `also_patch`: further ctypes tensor arrays (other
+        gradient sets of the same model) whose code pointers follow."""
         jobs, fresh = [], []
         for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
             n = self.param[l].numel()
-            for state, old, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
+            for state, cur, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
                 if b0 == b1:
                     continue
                 cb, _ = stq.state_bytes(n, self.w.K, b1)
-                dst = torch.empty(cb // 4, dtype=torch.int32, device=self.device)
-                jobs.append((n, state, old[l].data_ptr(), b0, dst.data_ptr(), b1))
-                fresh.append((old, l, dst))
+                spare = self._spare.get((l, state))
+                if spare is None or spare.numel() < cb // 4:
+                    cb_max, _ = stq.state_bytes(n, self.w.K, 8)
+                    spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
+                dst = spare[:cb // 4]
+                jobs.append((n, state, cur[l].data_ptr(), b0, dst.data_ptr(), b1))
+                fresh.append((cur, l, state, dst, spare))
         changed = len(jobs)
         if batched and jobs:
             self.ctx.repack_many(jobs, self.w.K, self.stream)
         else:
             for n, state, src, b0, dst, b1 in jobs:
                 self.ctx.repack(n, self.w.K, state, src, b0, dst, b1, self.stream)
-        for old, l, dst in fresh:   # the old buffers stay alive until the launches above are queued
-            old[l] = dst
+        for cur, l, state, dst, spare in fresh:
+            old = self._base.get((l, state), cur[l])   # whole allocation behind the current view
+            self._spare[(l, state)] = old
+            self._base[(l, state)] = spare
+            cur[l] = dst
+            for arr in (self.tensors,) + tuple(also_patch):
+                if state == 0:
+                    arr[l].m_codes = dst.data_ptr()
+                else:
+                    arr[l].v_codes = dst.data_ptr()
         self.plan = [tuple(p) for p in new_plan]
-        self._rebuild()
+        self.cplan = binding.make_plan(self.plan)
         return changed
 
     # ----------------------------------------------------------- host copies
