@@ -154,13 +154,17 @@ static float bf16_to_f32(uint16_t h) {
  *   grad  : fp32 (grad_bf16 = 0) or bf16 bit patterns (grad_bf16 = 1)
  *   um,sm : first-moment codes (one byte per element) and per-block scales, in/out
  *   cv,sv : second-moment codes and scales, in/out
- *   bm,bv : code widths in bits, 2..8
+ *   bm_old,bv_old : widths of the stored codes m_{t-1}, v_{t-1} (2..8)
+ *   bm,bv : widths b_{l,t} that Quantize uses in this step (2..8).  Algorithm 1 maps the
+ *           layer's new width before its layer loop, so in a step where the width changes
+ *           the stored moments are read at the old width and written at the new one; the
+ *           codes arrays hold one byte per element, so they are reused in place
  *   st    : if non-NULL, receives the statistics of this tensor for this step
  */
-void stq_oracle_step(float* param, const void* grad, int grad_bf16, uint64_t numel,
-                     uint8_t* um, float* sm, uint8_t* cv, float* sv,
-                     int bm, int bv, int K, const stq_oracle_hparams* hp,
-                     stq_oracle_stats* st) {
+void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint64_t numel,
+                            uint8_t* um, float* sm, uint8_t* cv, float* sv,
+                            int bm_old, int bv_old, int bm, int bv, int K,
+                            const stq_oracle_hparams* hp, stq_oracle_stats* st) {
   const float beta1 = hp->beta1, beta2 = hp->beta2;
   const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
   const float decay = 1.0f - hp->lr * hp->weight_decay;
@@ -184,8 +188,8 @@ void stq_oracle_step(float* param, const void* grad, int grad_bf16, uint64_t num
        where m_{t-1}, v_{t-1} are the stored (quantized) states */
     for (int i = 0; i < n; ++i) {
       g[i] = grad_bf16 ? bf16_to_f32(((const uint16_t*)grad)[lo + i]) : ((const float*)grad)[lo + i];
-      float mh = sm[j] * stq_oracle_R(bm, um[lo + i]);
-      float vh = sv[j] * stq_oracle_L(bv, cv[lo + i]);
+      float mh = sm[j] * stq_oracle_R(bm_old, um[lo + i]);
+      float vh = sv[j] * stq_oracle_L(bv_old, cv[lo + i]);
       float a = beta1 * mh, c = omb1 * g[i];
       m[i] = a + c;
       float gg = g[i] * g[i];
@@ -225,6 +229,14 @@ void stq_oracle_step(float* param, const void* grad, int grad_bf16, uint64_t num
     }
   }
   free(m); free(v); free(g);
+}
+
+/* The step with unchanged widths. */
+void stq_oracle_step(float* param, const void* grad, int grad_bf16, uint64_t numel,
+                     uint8_t* um, float* sm, uint8_t* cv, float* sv,
+                     int bm, int bv, int K, const stq_oracle_hparams* hp,
+                     stq_oracle_stats* st) {
+  stq_oracle_step_widths(param, grad, grad_bf16, numel, um, sm, cv, sv, bm, bv, bm, bv, K, hp, st);
 }
 
 /* ---------------------------------------------------------- storage layout

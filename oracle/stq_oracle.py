@@ -82,6 +82,11 @@ def lib():
         L.stq_oracle_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_int, C.c_int, C.c_int, C.POINTER(HParams), C.POINTER(Stats)]
+        L.stq_oracle_step_widths.restype = None
+        L.stq_oracle_step_widths.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                             C.POINTER(HParams), C.POINTER(Stats)]
         L.stq_oracle_code_words.restype = C.c_uint64
         L.stq_oracle_code_words.argtypes = [C.c_uint64, C.c_int]
         L.stq_oracle_pack.restype = None
@@ -196,6 +201,26 @@ def step(param: np.ndarray, grad: np.ndarray, st: State, *, lr, beta1, beta2, ep
     stats = Stats() if want_stats else None
     lib().stq_oracle_step(_p(param), _p(grad), int(bf16), st.numel, _p(st.um), _p(st.sm), _p(st.cv), _p(st.sv),
                           st.bm, st.bv, st.K, C.byref(hp), C.byref(stats) if want_stats else None)
+    return stats
+
+
+def step_transition(param: np.ndarray, grad: np.ndarray, st: State, bm_new: int, bv_new: int, *, lr, beta1, beta2,
+                    eps, weight_decay, t, want_stats: bool = False):
+    """The step in which the layer's widths change (Algorithm 1: Map, then the layer loop): the stored
+    moments are read at st.bm, st.bv and the new ones quantized at bm_new, bv_new.  Updates st in place,
+    including its widths."""
+    _chk(param, np.float32)
+    assert param.size == st.numel and grad.size == st.numel
+    bf16 = grad.dtype == np.uint16
+    if not bf16:
+        _chk(grad, np.float32)
+    assert grad.flags.c_contiguous
+    hp = HParams(lr, beta1, beta2, eps, weight_decay, t)
+    stats = Stats() if want_stats else None
+    lib().stq_oracle_step_widths(_p(param), _p(grad), int(bf16), st.numel, _p(st.um), _p(st.sm), _p(st.cv),
+                                 _p(st.sv), st.bm, st.bv, bm_new, bv_new, st.K, C.byref(hp),
+                                 C.byref(stats) if want_stats else None)
+    st.bm, st.bv = bm_new, bv_new
     return stats
 
 
