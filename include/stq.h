@@ -131,6 +131,26 @@ int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
 int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
              const stq_bits* bit_plan, const stq_hparams* hp, void* hip_stream);
 
+/* Destination of one tensor's new codes in stq_step_transition. */
+typedef struct {
+  void* m_codes; /* device, 256-byte aligned, sized by stq_state_bytes at the NEW width; may be NULL
+                    or the tensor's own m_codes when that width does not change */
+  void* v_codes;
+} stq_codes;
+
+/* The step in which Map's new plan takes effect, as Algorithm 1 is written: the
+ * layer's new width b_{l,t} is set before the layer loop, so the stored states
+ * m_{t-1}, v_{t-1} are read at the widths of plan_old (from tensors[l].m_codes /
+ * v_codes) and the new states are quantized and stored at the widths of plan_new,
+ * into new_codes[l] (scales stay in the tensor's scale arrays; a state whose width
+ * does not change may stay in place).  No separate conversion pass and no extra
+ * rounding of the old state.  A changed state's destination must not overlap its
+ * source.  Otherwise as stq_step; afterwards the caller uses plan_new and the new
+ * buffers. */
+int stq_step_transition(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
+                        const stq_bits* plan_old, const stq_bits* plan_new,
+                        const stq_codes* new_codes, const stq_hparams* hp, void* hip_stream);
+
 /* Copy accumulators 0..n-1 to `out` (host, n entries), synchronise, and clear
  * them on the device.  Sums are order-dependent in the last bits; the maxima
  * are exact. */

@@ -63,7 +63,11 @@ class RepackJob(C.Structure):
                 ("state", C.c_uint8), ("src_bits", C.c_uint8), ("dst_bits", C.c_uint8)]
 
 
-EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_stats",
+class Codes(C.Structure):
+    _fields_ = [("m_codes", C.c_void_p), ("v_codes", C.c_void_p)]
+
+
+EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_stats",
            "stq_repack", "stq_repack_many", "stq_decide", "stq_table", "stq_strerror"]
 
 _lib = None
@@ -87,6 +91,8 @@ def load_library():
     L.stq_state_bytes.argtypes = [u64, u32, u32, C.POINTER(u64), C.POINTER(u64)]
     L.stq_zero_state.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), u32, vp]
     L.stq_step.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(HParams), vp]
+    L.stq_step_transition.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(Bits),
+                                      C.POINTER(Codes), C.POINTER(HParams), vp]
     L.stq_stats.argtypes = [vp, C.POINTER(LayerStats), u32, vp]
     L.stq_repack.argtypes = [vp, u64, u32, C.c_int, vp, u32, vp, u32, vp]
     L.stq_repack_many.argtypes = [vp, C.POINTER(RepackJob), u32, u32, vp]
@@ -190,6 +196,14 @@ class Context:
     def step(self, tensors, plan, hp: HParams, stream: int = 0):
         _check(self._lib.stq_step(self._h, tensors, len(tensors), plan, C.byref(hp), C.c_void_p(stream)),
                "stq_step")
+
+    def step_transition(self, tensors, plan_old, plan_new, new_codes, hp: HParams, stream: int = 0):
+        """new_codes: sequence of (m_ptr or None, v_ptr or None), one per tensor."""
+        arr = (Codes * len(tensors))()
+        for a, (m, v) in zip(arr, new_codes):
+            a.m_codes, a.v_codes = m, v
+        _check(self._lib.stq_step_transition(self._h, tensors, len(tensors), plan_old, plan_new, arr,
+                                             C.byref(hp), C.c_void_p(stream)), "stq_step_transition")
 
     def stats(self, n: int, stream: int = 0):
         out = (LayerStats * n)()

@@ -90,6 +90,10 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
     d.n_tiles = static_cast<uint32_t>(nt);
     d.bm = plan[l].m_bits;
     d.bv = plan[l].v_bits;
+    d.m_out = d.m_codes;  // in place unless a caller redirects them
+    d.v_out = d.v_codes;
+    d.bm_out = d.bm;
+    d.bv_out = d.bv;
     tiles += nt;
   }
   *total_tiles = static_cast<uint32_t>(tiles);
@@ -243,13 +247,39 @@ int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const st
   return STQ_OK;
 }
 
-int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
-             const stq_hparams* hp, void* stream) {
+namespace {
+
+// One launch of the step kernel.  new_plan/new_codes are null for the in-place step.
+int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+              const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
   if (!hp) return STQ_EINVAL;
   if (hp->step == 0 || hp->grad_dtype > 1) return STQ_EINVAL;
   std::vector<TensorDesc> descs;
   uint32_t total = 0;
   if (int e = build_descs(ctx, tensors, n, plan, hp->block, true, descs, &total)) return e;
+  if (new_plan) {
+    for (uint32_t l = 0; l < n; ++l) {
+      TensorDesc& d = descs[l];
+      if (int e = check_bits(new_plan[l].m_bits)) return e;
+      if (int e = check_bits(new_plan[l].v_bits)) return e;
+      const uintptr_t span = static_cast<uintptr_t>(d.n_tiles) * 256;
+      struct { uint32_t b_old, b_new; uint32_t* cur; void* dst; uint32_t** out; } st[2] = {
+          {d.bm, new_plan[l].m_bits, d.m_codes, new_codes[l].m_codes, &d.m_out},
+          {d.bv, new_plan[l].v_bits, d.v_codes, new_codes[l].v_codes, &d.v_out}};
+      for (auto& x : st) {
+        if (x.b_new == x.b_old && (x.dst == nullptr || x.dst == x.cur)) continue;  // stays in place
+        // another width (or another buffer): the destination must be a distinct, aligned buffer
+        if (!x.dst) return STQ_EINVAL;
+        if (!aligned(x.dst, 256)) return STQ_EALIGN;
+        const uintptr_t s0 = reinterpret_cast<uintptr_t>(x.cur), s1 = s0 + span * x.b_old;
+        const uintptr_t d0 = reinterpret_cast<uintptr_t>(x.dst), d1 = d0 + span * x.b_new;
+        if (s0 < d1 && d0 < s1) return STQ_EINVAL;
+        *x.out = static_cast<uint32_t*>(x.dst);
+      }
+      d.bm_out = new_plan[l].m_bits;
+      d.bv_out = new_plan[l].v_bits;
+    }
+  }
   DeviceGuard g(ctx->device);
   if (!g.ok) return STQ_EHIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -299,10 +329,24 @@ int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits
   const uint64_t per_wave = (total + n_waves - 1) / n_waves;
   a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
-  if (launch_step(a, hp->grad_dtype == 1, want_stats, groups, stream) != 0) return STQ_EHIP;
+  if (launch_step(a, hp->grad_dtype == 1, want_stats, new_plan != nullptr, groups, stream) != 0) return STQ_EHIP;
   if (want_stats)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;
+}
+
+}  // namespace
+
+int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+             const stq_hparams* hp, void* stream) {
+  return step_impl(ctx, tensors, n, plan, nullptr, nullptr, hp, stream);
+}
+
+int stq_step_transition(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan_old,
+                        const stq_bits* plan_new, const stq_codes* new_codes, const stq_hparams* hp,
+                        void* stream) {
+  if (!plan_new || !new_codes) return STQ_EINVAL;
+  return step_impl(ctx, tensors, n, plan_old, plan_new, new_codes, hp, stream);
 }
 
 int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* stream) {

@@ -19,7 +19,10 @@ struct TensorDesc {
   uint64_t numel;
   uint32_t tile_begin;  // index of this tensor's first tile in the launch-wide tile order
   uint32_t n_tiles;
-  uint32_t bm, bv;
+  uint32_t bm, bv;      // widths of the stored codes
+  uint32_t* m_out;      // where the new codes go: the same buffers, or others when a width changes
+  uint32_t* v_out;
+  uint32_t bm_out, bv_out;
 };
 
 // Accumulator slots (doubles unless noted).
@@ -75,7 +78,8 @@ struct RepackManyArgs {
 };
 
 // Launchers implemented in stq_step.hip and stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
-int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream);
+int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, bool changes_widths, uint32_t groups,
+                void* stream);
 int launch_zero(const ZeroArgs& a, void* stream);
 int launch_repack(const RepackArgs& a, void* stream);
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream);

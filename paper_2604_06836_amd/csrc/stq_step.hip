@@ -314,7 +314,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
 // Lane L = (value vL = L>>4, lane group qL = L&15) owns one (state, row) pair's block scale:
 // state = vL>>1, row = 2q + (vL&1), block within the row = qL >> (lgK-4).  A block's owners are
 // 4, 8 or 16 neighbouring lanes of one 16-lane row, so their maxima combine by DPP lane swaps.
-template <bool BF16, bool STATS, bool TAIL>
+template <bool BF16, bool STATS, bool TAIL, bool XW>
 __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t tile, uint32_t q, uint32_t n_valid,
                                                 const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
                                                 uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
@@ -324,13 +324,19 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   asm volatile("" : "+v"(lane));
   uint32_t lgK = a.lgK;
   asm volatile("" : "+s"(lgK));
-  const uint32_t bm = d.bm, bv = d.bv;
+  const uint32_t bm = d.bm, bv = d.bv;              // widths of the stored codes
+  // widths this step writes: the same, unless the launch changes widths (XW)
+  const uint32_t bmo = XW ? d.bm_out : bm, bvo = XW ? d.bv_out : bv;
   const size_t e0 = static_cast<size_t>(tile) * kTile + 512u * q;
   STQ_GLOBAL float* P = as_global(d.param + e0);
   // the quarter's first bit: word (q*b)>>2 of the lane's b words, bit 8*((q*b)&3)
   const uint32_t s0m = 8u * ((q * bm) & 3u), s0v = 8u * ((q * bv) & 3u);
   STQ_GLOBAL uint32_t* CM = as_global(d.m_codes + static_cast<size_t>(tile) * 64u * bm) + ((q * bm) >> 2) * 64;
   STQ_GLOBAL uint32_t* CV = as_global(d.v_codes + static_cast<size_t>(tile) * 64u * bv) + ((q * bv) >> 2) * 64;
+  // where the new codes go: the same buffers at the same widths, or other buffers at the new widths
+  const uint32_t s0mo = 8u * ((q * bmo) & 3u), s0vo = 8u * ((q * bvo) & 3u);
+  STQ_GLOBAL uint32_t* CMO = XW ? as_global(d.m_out + static_cast<size_t>(tile) * 64u * bmo) + ((q * bmo) >> 2) * 64 : CM;
+  STQ_GLOBAL uint32_t* CVO = XW ? as_global(d.v_out + static_cast<size_t>(tile) * 64u * bvo) + ((q * bvo) >> 2) * 64 : CV;
   const size_t sbase = static_cast<size_t>(tile) << (11 - lgK);  // scales per tile = 2048/K
   // the lane index as a 6-bit unsigned offset: global addresses become uniform base + 32-bit offset
   const uint32_t ul = static_cast<uint32_t>(lane) & 63u;
@@ -483,12 +489,12 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   wave_lds_sync();
 
   // ---- table of den = sqrt(vq*ibc2) + eps and 1/den per (row, block, second-moment code) ----
-  // Used when a level serves at least four elements: entries = (512/K) << bv <= 128.  The table
+  // Used when a level serves at least four elements: entries = (512/K) << bv_out <= 128.  The table
   // takes the place of XR, whose last readers have finished.
   const UpdateArgs ua = {a.ibc1, a.ibc2, a.eps, a.lr, a.decay};
-  const uint32_t n_entries = (512u >> lgK) << bv;
+  const uint32_t n_entries = (512u >> lgK) << bvo;
   const bool use_table = n_entries <= kDenEntries;
-  const uint32_t l_base = 4u << bv;
+  const uint32_t l_base = 4u << bvo;
   float2* DEN = reinterpret_cast<float2*>(XR);
   // The short forms of the quotient (and, without a table, of the square root) need every operand
   // in a range where no intermediate underflows or overflows.  The owner lanes check their scales:
@@ -505,7 +511,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   bool fast_div;
   if (use_table) {
     for (uint32_t e = lane; e < n_entries; e += 64) {
-      const uint32_t c = e & ((1u << bv) - 1u), rg = e >> bv;
+      const uint32_t c = e & ((1u << bvo) - 1u), rg = e >> bvo;
       const uint32_t row = rg >> (8 - lgK), blk = rg & ((1u << (8 - lgK)) - 1u);
       const float sv = SN[((blk << (lgK - 4)) << 2) + 2 + row];
       const float vq = sv * lds_at(Lreg, (c << 2) | l_base);
@@ -530,9 +536,9 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       const float4 b0 = *reinterpret_cast<const float4*>(SI + (lane >> 2) * 4);
       sn[0] = a0.x; sn[1] = a0.y; inv[0] = b0.x; inv[1] = b0.y;
     }
-    const int qmax = (1 << (bm - 1)) - 1;
+    const int qmax = (1 << (bmo - 1)) - 1;
     const float qmaxf = static_cast<float>(qmax);
-    const uint32_t r_base = 4u << bm;
+    const uint32_t r_base = 4u << bmo;
     uint32_t code[8];
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
@@ -555,7 +561,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       }
       m[n] = mq;
     }
-    STQ_SWITCH_BITS(bm, (pack_store<B>(code, CM, s0m, carry_m, ul)));
+    STQ_SWITCH_BITS(bmo, (pack_store<B>(code, CMO, s0mo, carry_m, ul)));
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
@@ -566,12 +572,12 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       const float4 b1 = *reinterpret_cast<const float4*>(SI + (lane >> 2) * 4);
       sn[0] = a1.z; sn[1] = a1.w; inv[0] = b1.z; inv[1] = b1.w;
     }
-    const uint2* VQ = reinterpret_cast<const uint2*>(lds + kTabVqOff) + (bv - 2) * kVqBuckets;
-    // den table entry ((row*G + block) << bv) + c, G = 256/K blocks per row
+    const uint2* VQ = reinterpret_cast<const uint2*>(lds + kTabVqOff) + (bvo - 2) * kVqBuckets;
+    // den table entry ((row*G + block) << bv_out) + c, G = 256/K blocks per row
     uint32_t den_row[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bv);
+      den_row[i] = (((static_cast<uint32_t>(i) << (8 - lgK)) + (static_cast<uint32_t>(lane) >> (lgK - 2))) << bvo);
     uint32_t code[8];
     if (use_table) {
       if (fast_div)
@@ -584,7 +590,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       else
         quant2_update<STATS, TAIL, false, false>(v, m, theta, code, sn, inv, Lreg, l_base, VQ, DEN, den_row, ua, q, lane, n_valid, st);
     }
-    STQ_SWITCH_BITS(bv, (pack_store<B>(code, CV, s0v, carry_v, ul)));
+    STQ_SWITCH_BITS(bvo, (pack_store<B>(code, CVO, s0vo, carry_v, ul)));
   }
 
 #pragma unroll
@@ -606,7 +612,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #define STQ_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ TensorDesc load_desc(const TensorDesc* table, uint32_t l) {
   const STQ_CONSTANT uint64_t* p = (const STQ_CONSTANT uint64_t*)(table + l);
-  static_assert(sizeof(TensorDesc) == 72 || sizeof(TensorDesc) == 80, "descriptor layout");
+  static_assert(sizeof(TensorDesc) == 96, "descriptor layout");
   uint64_t w[sizeof(TensorDesc) / 8];
 #pragma unroll
   for (size_t i = 0; i < sizeof(TensorDesc) / 8; ++i) w[i] = p[i];
@@ -627,7 +633,7 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // contiguous range: few tensors per wave).
 // The statistics variant needs about 80 more registers and runs one workgroup per CU at a time
 // (a second workgroup of six waves per CU measured slower).
-template <bool BF16, bool STATS>
+template <bool BF16, bool STATS, bool XW>
 __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
@@ -668,11 +674,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kerne
       if (left >= static_cast<uint64_t>(kTile)) {
 #pragma nounroll
         for (uint32_t q = 0; q < 4; ++q)
-          process_quarter<BF16, STATS, false>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
+          process_quarter<BF16, STATS, false, XW>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
       } else {
 #pragma nounroll
         for (uint32_t q = 0; q < 4; ++q)
-          process_quarter<BF16, STATS, true>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
+          process_quarter<BF16, STATS, true, XW>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
                                              carry_v, st);
       }
       if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
@@ -683,16 +689,23 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kerne
 
 }  // namespace
 
-int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, uint32_t groups, void* stream) {
+template <bool XW>
+static void launch_variant(const StepArgs& a, bool grad_bf16, bool want_stats, dim3 grid, dim3 block, hipStream_t s) {
+  if (grad_bf16) {
+    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true, XW>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<true, false, XW>), grid, block, 0, s, a);
+  } else {
+    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true, XW>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<false, false, XW>), grid, block, 0, s, a);
+  }
+}
+
+int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, bool changes_widths, uint32_t groups,
+                void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(groups), block(64 * kWavesPerGroup);
-  if (grad_bf16) {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<true, false>), grid, block, 0, s, a);
-  } else {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<false, false>), grid, block, 0, s, a);
-  }
+  if (changes_widths) launch_variant<true>(a, grad_bf16, want_stats, grid, block, s);
+  else launch_variant<false>(a, grad_bf16, want_stats, grid, block, s);
   return static_cast<int>(hipGetLastError());
 }
 

@@ -270,6 +270,64 @@ def test_scaled_configs(oracle, ctx, name):
     run_both(oracle, ctx, w, w.initial_plan(), 4, stats_steps=(4,), tag=name)
 
 
+# ------------------------------------------------------- step with a change of widths
+@pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64), ("fp32", 256)])
+def test_step_transition_every_width_pair(oracle, ctx, dtype, K):
+    # 49 tensors: tensor i changes m from 2+i//7 to 2+i%7 bits and v from 2+i%7 to 2+i//7 bits
+    # (the diagonal keeps its widths and stays in place), after two ordinary steps; ragged sizes
+    sizes = [3 * 2048 + 517, 2048, 4096 + 1, 700, 5 * 2048]
+    tensors = [(f"t{i}", sizes[i % len(sizes)] + i) for i in range(49)]
+    w = configs.Workload(95, f"trans-{dtype}-{K}", tensors, K, dtype, 4, "normal_per_tensor")
+    old = [(2 + i // 7, 2 + i % 7) for i in range(49)]
+    new = [(2 + i % 7, 2 + i // 7) for i in range(49)]
+    dm = DeviceModel(ctx, w, old)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, old)
+    for t in (1, 2):
+        dm.set_grads(t)
+        dm.step(t)
+        for l in range(49):
+            oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t)
+    dm.set_grads(3)
+    changed = dm.step_transition(3, new, stats=True)
+    torch.cuda.synchronize()
+    assert changed == 2 * 42
+    gs = dm.ctx.stats(49, dm.stream)
+    for l in range(49):
+        s = oracle.step_transition(th_ref[l], dm.host_grad(l), st_ref[l], *new[l], **w.hparams, t=3, want_stats=True)
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"transition tensor {l} {old[l]}->{new[l]}")
+        assert_stats_close(gs[l], s, f"transition tensor {l}")
+    # and the model keeps stepping at the new widths
+    dm.set_grads(4)
+    dm.step(4)
+    torch.cuda.synchronize()
+    for l in range(49):
+        oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=4)
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"after transition tensor {l}")
+
+
+def test_step_transition_argument_checks(ctx):
+    w = configs.Workload(96, "targs", [("a", 4096)], 128, "fp32", 1, "normal")
+    dm = DeviceModel(ctx, w, [(8, 4)])
+    lib = stq.load_library()
+    import ctypes as C
+    hp = hparams(w, 1)
+    cb, _ = stq.state_bytes(4096, 128, 5)
+    dst = torch.empty(cb // 4 + 64, dtype=torch.int32, device="cuda")
+
+    def call(new_plan, m, v):
+        arr = (binding.Codes * 1)(binding.Codes(m, v))
+        return lib.stq_step_transition(ctx._h, dm.tensors, 1, dm.cplan, binding.make_plan(new_plan), arr, C.byref(hp), None)
+
+    assert call([(5, 4)], None, None) == -1                           # a changed width needs a destination
+    assert call([(5, 4)], dm.m_codes[0].data_ptr(), None) == -1      # ... that is not the source
+    assert call([(5, 4)], dst.data_ptr() + 4, None) == -2            # ... and is aligned
+    assert call([(9, 4)], dst.data_ptr(), None) == -3
+    assert lib.stq_step_transition(ctx._h, dm.tensors, 1, dm.cplan, None, None, C.byref(hp), None) == -1
+    assert call([(5, 4)], dst.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+
+
 # --------------------------------------------------------------------- argument checks
 def test_argument_checks(ctx):
     w = configs.Workload(94, "args", [("a", 4096)], 128, "fp32", 1, "normal")

@@ -109,6 +109,41 @@ class DeviceModel:
         self.cplan = binding.make_plan(self.plan)
         return changed
 
+    def step_transition(self, t: int, new_plan: Sequence[Tuple[int, int]], stats: bool = False, also_patch=()) -> int:
+        """One step that reads the states at the current plan and writes them at new_plan
+        (stq_step_transition), then adopts the new buffers and plan.  Returns the number of changed states."""
+        dests, fresh = [], []
+        for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
+            n = self.param[l].numel()
+            ptrs = [None, None]
+            for state, cur, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
+                if b0 == b1:
+                    continue
+                cb, _ = stq.state_bytes(n, self.w.K, b1)
+                spare = self._spare.get((l, state))
+                if spare is None or spare.numel() < cb // 4:
+                    cb_max, _ = stq.state_bytes(n, self.w.K, 8)
+                    spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
+                dst = spare[:cb // 4]
+                ptrs[state] = dst.data_ptr()
+                fresh.append((cur, l, state, dst, spare))
+            dests.append(tuple(ptrs))
+        new_cplan = binding.make_plan(new_plan)
+        self.ctx.step_transition(self.tensors, self.cplan, new_cplan, dests, hparams(self.w, t, stats), self.stream)
+        for cur, l, state, dst, spare in fresh:
+            old = self._base.get((l, state), cur[l])
+            self._spare[(l, state)] = old
+            self._base[(l, state)] = spare
+            cur[l] = dst
+            for arr in (self.tensors,) + tuple(also_patch):
+                if state == 0:
+                    arr[l].m_codes = dst.data_ptr()
+                else:
+                    arr[l].v_codes = dst.data_ptr()
+        self.plan = [tuple(p) for p in new_plan]
+        self.cplan = new_cplan
+        return len(fresh)
+
     # ----------------------------------------------------------- host copies
     def host_state(self, l: int):
         """(param, m_code_words, m_scales, v_code_words, v_scales) of tensor l as numpy arrays."""
