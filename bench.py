@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--transition", choices=("repack", "fused"), default="repack",
+                    help="how a new bit plan takes effect: stq_repack_many before the step (the configurations' "
+                         "wording), or inside the step with stq_step_transition")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise kernel of known size (scale reference for HBM counters)")
     args = ap.parse_args()
@@ -120,20 +123,29 @@ def main():
     ladder = None
     kernel_ms, repacked = [], 0
 
+    fused = args.transition == "fused"
+    pending = None  # fused mode: the plan that the next step adopts
+
     def one_step(t, timed):
-        nonlocal plan, ladder, repacked
+        nonlocal plan, ladder, repacked, pending
         k = t % 2
         dm.grad = grads[k]
+        dm.tensors = tensor_sets[k]
         if w.transitions == "switch10pct_every5":
             new_plan = w.switch_plan(plan, t)
             if new_plan != plan:
-                dm.tensors = tensor_sets[k]
-                repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
-                plan = new_plan
-        dm.tensors = tensor_sets[k]
+                if fused:
+                    pending = new_plan
+                else:
+                    repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
+                    plan = new_plan
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        dm.step(t, stats=decide_every_step)
+        if pending is not None:
+            repacked += dm.step_transition(t, pending, stats=decide_every_step, also_patch=(tensor_sets[1 - k],))
+            plan, pending = pending, None
+        else:
+            dm.step(t, stats=decide_every_step)
         e1.record(stream)
         if timed:
             kernel_ms.append((e0, e1))
@@ -143,8 +155,11 @@ def main():
                 _, sc = stq.decide(binding.DecideState(0, 0, 0), st, t, alpha=0.3, tau=4.0, thr=(), bits=(4,))
                 ladder = calibrate_ladder(sc, w.p_m)
             new_plan, _ = stq.decide(ema, st, t, alpha=0.3, tau=4.0, v_offset=-0.5, thr=ladder, bits=w.bits_m)
-            repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
-            plan = new_plan
+            if fused:
+                pending = new_plan if new_plan != plan else None
+            else:
+                repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
+                plan = new_plan
 
     t = 0
     for _ in range(args.warmup):
@@ -176,7 +191,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "configs_index": w.cfg, "params": n, "tensors": L, "block": w.K,
                    "grad_dtype": w.grad_dtype, "avg_state_bits": round(w.avg_bits(plan), 3),
-                   "repacked_states_in_timed_region": repacked},
+                   "transition": args.transition, "changed_states_in_timed_region": repacked},
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel_ms_avg": k_avg_ms, "algorithmic_bytes_per_param": bpp,

@@ -34,7 +34,7 @@ namespace {
 constexpr int XS = 68;  // row stride (words) of the transpose scratch: keeps 16-byte alignment, shifts banks
 // per-wave LDS scratch: XR[4][XS] partial maxima (later the den table), old scales, new scales, reciprocals
 constexpr int kWaveScratch = 4 * XS + 3 * 64;
-constexpr int kLdsWords = kTabWords + kWavesPerGroup * kWaveScratch;
+constexpr int kLdsWords = kTabWords + kWavesPerGroup * kWaveScratch;  // + the statistics slices in that variant
 constexpr int kStatFlushTiles = 16;  // fp32 lane sums are widened to fp64 every this many tiles
 constexpr uint32_t kDenEntries = 128;  // capacity of the per-wave den table (8 bytes per entry, inside XR)
 
@@ -129,20 +129,31 @@ __device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n
 }
 
 // -------------------------------------------------------------------- statistics
+// Running statistics of one wave, kept in its LDS slice so that they cost no registers between
+// the places that add to them: slot k of lane j is acc[k*64 + j].  Slots 0..8 are fp32 sums of the
+// lane since the last widening, 9..11 running maxima (as bit patterns: all are non-negative)
+// since the last flush; lane k < 9 of slot 12/13 holds the fp64 total of sum k for the current tensor.
+enum LaneSlot { kLGSum = 0, kLGAbs, kLGSq, kLMSum, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr, kLGMax, kLMMax, kLVMax, kLWide };
+constexpr int kStatLdsWords = 14 * 64;
 struct LaneStats {
-  // fp32 running sums of this lane since the last widening, and running maxima since the last flush
-  float g_sum, g_abs, g_sq, m_sum, m_sq, m_err, v_sum, v_sq, v_err;
-  float g_max, m_max, v_max;
-  double wide;  // lane k < 9 holds the fp64 total of sum k for the current tensor
-  uint32_t tiles;
-  __device__ __forceinline__ void clear_sums() {
-    g_sum = g_abs = g_sq = m_sum = m_sq = m_err = v_sum = v_sq = v_err = 0.0f;
+  float* acc;      // this wave's slice, null in the plain kernel
+  uint32_t tiles;  // tiles since the last widening (uniform)
+  __device__ __forceinline__ void add(int slot, int lane, float x) { acc[slot * 64 + lane] += x; }
+  __device__ __forceinline__ void max_bits(int slot, int lane, float x) {
+    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + slot * 64 + lane;
+    *p = max(*p, f2u(x));
+  }
+  __device__ __forceinline__ double& wide(int lane) { return reinterpret_cast<double*>(acc + kLWide * 64)[lane]; }
+  __device__ __forceinline__ void clear_sums(int lane) {
+#pragma unroll
+    for (int k = 0; k < 9; ++k) acc[k * 64 + lane] = 0.0f;
     tiles = 0;
   }
-  __device__ __forceinline__ void clear_all() {
-    clear_sums();
-    g_max = m_max = v_max = 0.0f;
-    wide = 0.0;
+  __device__ __forceinline__ void clear_all(int lane) {
+    clear_sums(lane);
+#pragma unroll
+    for (int k = 9; k < 12; ++k) acc[k * 64 + lane] = 0.0f;
+    wide(lane) = 0.0;
   }
 };
 
@@ -159,19 +170,19 @@ __device__ __forceinline__ float wave_max(float x) {
 
 // fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
 __device__ __forceinline__ void widen_stats(LaneStats& s, int lane) {
-  const float v[9] = {s.g_sum, s.g_abs, s.g_sq, s.m_sum, s.m_sq, s.m_err, s.v_sum, s.v_sq, s.v_err};
 #pragma unroll
   for (int k = 0; k < 9; ++k) {
-    const double t = wave_sum(static_cast<double>(v[k]));
-    if (lane == k) s.wide += t;
+    const double t = wave_sum(static_cast<double>(s.acc[k * 64 + lane]));
+    if (lane == k) s.wide(lane) += t;
   }
-  s.clear_sums();
+  s.clear_sums(lane);
 }
 
 __device__ __forceinline__ void flush_stats(LaneStats& s, double* slot, int lane) {
   widen_stats(s, lane);
-  const float gm = wave_max(s.g_max), mm = wave_max(s.m_max), vm = wave_max(s.v_max);
-  if (lane < 9) atomicAdd(&slot[lane], s.wide);
+  const float gm = wave_max(s.acc[kLGMax * 64 + lane]), mm = wave_max(s.acc[kLMMax * 64 + lane]),
+              vm = wave_max(s.acc[kLVMax * 64 + lane]);
+  if (lane < 9) atomicAdd(&slot[lane], s.wide(lane));
   if (lane == 0) {
     // non-negative floats order like their bit patterns
     uint32_t* mx = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);
@@ -179,7 +190,7 @@ __device__ __forceinline__ void flush_stats(LaneStats& s, double* slot, int lane
     atomicMax(&mx[1], f2u(mm));
     atomicMax(&mx[2], f2u(vm));
   }
-  s.clear_all();
+  s.clear_all(lane);
 }
 
 // x from the lane that a DPP control word names (all lanes of the wave active)
@@ -272,6 +283,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
                                               const uint32_t (&den_row)[2], const UpdateArgs& u, uint32_t q, int lane,
                                               uint32_t n_valid, LaneStats& st) {
+  float sv_sum = 0.0f, sv_sq = 0.0f, sv_err = 0.0f;  // this quarter's part of the lane sums
 #pragma unroll
   for (int n = 0; n < 8; ++n) {
     const int i = n >> 2;
@@ -286,9 +298,9 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
       const float d = v[n] - vq;
-      st.v_sum += v[n];
-      st.v_sq += v[n] * v[n];
-      st.v_err += d * d;
+      sv_sum += v[n];
+      sv_sq += v[n] * v[n];
+      sv_err += d * d;
     }
     const float mt = mq[n] * u.ibc1;
     if (TABLE) {
@@ -307,6 +319,11 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
         theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, u);
       }
     }
+  }
+  if (STATS) {
+    st.add(kLVSum, lane, sv_sum);
+    st.add(kLVSq, lane, sv_sq);
+    st.add(kLVErr, lane, sv_err);
   }
 }
 
@@ -398,13 +415,18 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   }
 
   if (STATS) {
+    float sg_sum = 0.0f, sg_abs = 0.0f, sg_sq = 0.0f, sg_max = 0.0f;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      st.g_sum += g[n];
-      st.g_abs += fabsf(g[n]);
-      st.g_sq += g[n] * g[n];
-      st.g_max = fmaxf(st.g_max, fabsf(g[n]));
+      sg_sum += g[n];
+      sg_abs += fabsf(g[n]);
+      sg_sq += g[n] * g[n];
+      sg_max = fmaxf(sg_max, fabsf(g[n]));
     }
+    st.add(kLGSum, lane, sg_sum);
+    st.add(kLGAbs, lane, sg_abs);
+    st.add(kLGSq, lane, sg_sq);
+    st.max_bits(kLGMax, lane, sg_max);
   }
 
   // ---- moments: m_t = beta1*m_{t-1} + (1-beta1)*g ; v_t = beta2*v_{t-1} + (1-beta2)*g^2 ----
@@ -473,7 +495,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     r = u2f(rb);
   }
   if (STATS) {
-    if (vL < 2) st.m_max = fmaxf(st.m_max, r); else st.v_max = fmaxf(st.v_max, r);
+    st.max_bits(vL < 2 ? kLMMax : kLVMax, lane, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
@@ -540,6 +562,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     const float qmaxf = static_cast<float>(qmax);
     const uint32_t r_base = 4u << bmo;
     uint32_t code[8];
+    float sm_sum = 0.0f, sm_sq = 0.0f, sm_err = 0.0f;  // this quarter's part of the lane sums
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int i = n >> 2;
@@ -555,11 +578,16 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (STATS) {
         if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
         const float dd = m[n] - mq;
-        st.m_sum += m[n];
-        st.m_sq += m[n] * m[n];
-        st.m_err += dd * dd;
+        sm_sum += m[n];
+        sm_sq += m[n] * m[n];
+        sm_err += dd * dd;
       }
       m[n] = mq;
+    }
+    if (STATS) {
+      st.add(kLMSum, lane, sm_sum);
+      st.add(kLMSq, lane, sm_sq);
+      st.add(kLMErr, lane, sm_err);
     }
     STQ_SWITCH_BITS(bmo, (pack_store<B>(code, CMO, s0mo, carry_m, ul)));
   }
@@ -634,9 +662,9 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // The statistics variant needs about 80 more registers and runs one workgroup per CU at a time
 // (a second workgroup of six waves per CU measured slower).
 template <bool BF16, bool STATS, bool XW>
-__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kernel(const StepArgs a) {
+__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
-  __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords];
+  __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + (STATS ? kWavesPerGroup * kStatLdsWords : 0)];
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
   __syncthreads();
 
@@ -659,7 +687,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 2 : 6) void step_kerne
   TensorDesc d = load_desc(a.desc, l);
 
   LaneStats st;
-  if (STATS) st.clear_all();
+  st.acc = STATS ? reinterpret_cast<float*>(lds + kLdsWords + wave * kStatLdsWords) : nullptr;
+  st.tiles = 0;
+  if (STATS) st.clear_all(lane);
   for (; base < a.total_tiles; base += n_waves * C) {
     const uint32_t c_end = static_cast<uint32_t>(min(base + C, static_cast<uint64_t>(a.total_tiles)));
     for (uint32_t t = static_cast<uint32_t>(base); t < c_end; ++t) {
