@@ -106,3 +106,39 @@ def test_full_size_sampled_parity(oracle, name):
     ctx.close()
     del dm
     torch.cuda.empty_cache()
+
+
+def test_tensor_beyond_2_31_elements(oracle):
+    """One tensor of 2^31 + 4099 elements next to a small one: element, byte and code-word offsets
+    pass 2^31 and 2^32.  Windows around those boundaries and the ragged tail are compared with the oracle."""
+    n_big = (1 << 31) + 4099
+    w = configs.Workload(97, "huge", [("small", 70_001), ("big", n_big)], 64, "bf16", 2, "normal")
+    plan = [(5, 6), (8, 3)]
+    ctx = stq.Context(0, 4)
+    dm = DeviceModel(ctx, w, plan, init_params=False)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(12345)
+    for l in range(2):
+        dm.param[l].normal_(0.0, 0.02, generator=gen)
+    nt = (n_big + TILE - 1) // TILE
+    tiles = [0, (1 << 29) // TILE - 1, (1 << 30) // TILE - 1, (1 << 31) // TILE - 2, (1 << 31) // TILE - 1, nt - 2]
+    windows = [(0, 0, 70_001)] + [(1, t0 * TILE, min(2 * TILE, n_big - t0 * TILE)) for t0 in tiles]
+    for t in (1, 2):
+        for l in range(2):   # gradients drawn on the device: the host generator would take minutes here
+            dm.grad[l].copy_(torch.empty(dm.grad[l].numel(), dtype=torch.float32, device="cuda")
+                             .normal_(0.0, 1e-3 * (l + 1), generator=gen))
+        before = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
+        dm.step(t, stats=(t == 2))
+        torch.cuda.synchronize()
+        for (l, lo, n), (th, g, st) in zip(windows, before):
+            oracle.step(th, g, st, **w.hparams, t=t)
+            check_window(oracle, dm, w, l, lo, n, th, st, f"huge step {t} tensor {l} window {lo}+{n}")
+    gs = ctx.stats(2, dm.stream)
+    assert gs[1].count == n_big and gs[0].count == 70_001
+    g64 = dm.grad[1].double()
+    assert abs(gs[1].g_sq_sum - float((g64 * g64).sum())) <= 1e-5 * float((g64 * g64).sum())
+    assert gs[1].g_absmax == float(g64.abs().max())
+    del g64
+    ctx.close()
+    del dm
+    torch.cuda.empty_cache()
