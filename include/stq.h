@@ -98,12 +98,16 @@ typedef struct { double n_ema, r_ema, v_ema; } stq_decide_state;
  * second-moment width is mapped from score + v_offset. */
 typedef struct {
   double alpha, tau, phi, eps, v_offset;
-  uint32_t flags;  /* bit 0: r_l = sigma(g)/(E|g|+eps) as in Algorithm 1 instead of Eq. 3's CV of |g| */
+  uint32_t flags;  /* bit 0: r_l = sigma(g)/(E|g|+eps) as in Algorithm 1 instead of Eq. 3's CV of |g|;
+                      bits 1..3: the ablations of the paper's component study, see below */
   uint32_t n_thr;
   const double* thr;   /* host, ascending */
   const uint8_t* bits; /* host */
 } stq_decide_cfg;
 #define STQ_DECIDE_R_ALG1 1u
+#define STQ_DECIDE_NO_DUAL 2u     /* score without the intensity and variation terms ("w/o Dual Factor") */
+#define STQ_DECIDE_NO_TEMPORAL 4u /* score without log2 S_t ("w/o Temporal Factor") */
+#define STQ_DECIDE_NO_SPATIAL 8u  /* score without log2(v_l / v_global) ("w/o Spatial Factor") */
 
 /* Create a context on HIP device `device` (must be gfx950) for up to
  * max_tensors tensors per call.  Builds the level/threshold tables of the two
@@ -187,6 +191,10 @@ int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32
 int stq_decide(stq_decide_state* ema, const stq_layer_stats* stats, uint32_t n,
                const stq_decide_cfg* cfg, uint32_t step, stq_bits* plan_out,
                double* score_out);
+
+/* Algorithm 1's update cadence: 1 when the decision runs at step t (t mod U = 0, or t < 5), else 0.
+ * U = 0 means "only during the first steps". */
+int stq_decide_due(uint32_t step, uint32_t update_every);
 
 /* The library's own quantizer tables, for inspection (host only, no context):
  *   which 0: G[j] = fl32(2^(-j/32)), j < 511 (bits ignored)

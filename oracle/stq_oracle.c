@@ -331,6 +331,7 @@ void stq_oracle_repack(const uint8_t* in, uint64_t numel, int state /*0 = m line
  * (Eq. 7), the score of Sec. 3.4 with Alg. 1's eps in the denominators, and the
  * step function Map: width = bits[ number of thresholds <= score ].
  * The second-moment width uses score + v_offset.
+ * The update cadence of Alg. 1 (decide when t mod U = 0 or t < 5) is stq_oracle_decide_due.
  */
 typedef struct { double n_ema, r_ema, v_ema; } stq_oracle_ema;
 
@@ -338,9 +339,15 @@ typedef struct {
   double alpha, tau, phi, eps, v_offset;
   int r_mode;       /* 0: Eq. 3, 1: Alg. 1 line for r_l */
   int n_thr;        /* number of thresholds; bits has n_thr+1 entries */
+  int drop;         /* ablations of Sec. 4 (Table "w/o ..."): bit 0 drops the dual factor (the
+                       intensity and variation terms), bit 1 the temporal term log2 S_t, bit 2 the
+                       spatial term log2(v_l / v_global) */
+  int pad_;
   const double* thr;
   const uint8_t* bits;
 } stq_oracle_decide_cfg;
+
+int stq_oracle_decide_due(uint32_t step, uint32_t U) { return (U != 0 && step % U == 0) || step < 5; }
 
 static uint8_t map_score(double score, const stq_oracle_decide_cfg* c) {
   int k = 0;
@@ -373,8 +380,10 @@ void stq_oracle_decide(stq_oracle_ema* ema, const stq_oracle_stats* st, int L,
   ema->v_ema = c->alpha * av + (1.0 - c->alpha) * ema->v_ema;
   double S = 1.0 + 1.0 / cosh((double)step / c->tau);
   for (int l = 0; l < L; ++l) {
-    double score = c->phi + log2(r[l] / (ema->r_ema + c->eps)) + log2(n[l] / (ema->n_ema + c->eps))
-                 + log2(S) + log2(v[l] / (ema->v_ema + c->eps));
+    double score = c->phi;
+    if (!(c->drop & 1)) score += log2(r[l] / (ema->r_ema + c->eps)) + log2(n[l] / (ema->n_ema + c->eps));
+    if (!(c->drop & 2)) score += log2(S);
+    if (!(c->drop & 4)) score += log2(v[l] / (ema->v_ema + c->eps));
     if (score_out) score_out[l] = score;
     bits_m[l] = map_score(score, c);
     bits_v[l] = map_score(score + c->v_offset, c);

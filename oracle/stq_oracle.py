@@ -55,6 +55,7 @@ class Ema(C.Structure):
 class DecideCfg(C.Structure):
     _fields_ = [("alpha", C.c_double), ("tau", C.c_double), ("phi", C.c_double), ("eps", C.c_double),
                 ("v_offset", C.c_double), ("r_mode", C.c_int), ("n_thr", C.c_int),
+                ("drop", C.c_int), ("pad_", C.c_int),
                 ("thr", C.POINTER(C.c_double)), ("bits", C.POINTER(C.c_uint8))]
 
 
@@ -96,6 +97,8 @@ def lib():
         L.stq_oracle_repack.restype = None
         L.stq_oracle_repack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.stq_oracle_decide.restype = None
+        L.stq_oracle_decide_due.restype = C.c_int
+        L.stq_oracle_decide_due.argtypes = [C.c_uint32, C.c_uint32]
         L.stq_oracle_decide.argtypes = [C.POINTER(Ema), C.POINTER(Stats), C.c_int, C.POINTER(DecideCfg),
                                         C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -265,14 +268,18 @@ PAPER_BITS = (4, 8, 16, 32)
 PAPER_PHI = 7.2
 
 
+def decide_due(step_t: int, U: int) -> bool:
+    return bool(lib().stq_oracle_decide_due(step_t, U))
+
+
 def decide(ema: Ema, stats: list, step_t: int, *, alpha=0.1, tau=1000.0, phi=PAPER_PHI, eps=1e-12,
-           v_offset=0.0, r_mode=0, thr=PAPER_THRESHOLDS, bits=PAPER_BITS):
+           v_offset=0.0, r_mode=0, thr=PAPER_THRESHOLDS, bits=PAPER_BITS, drop=0):
     L = len(stats)
     arr = (Stats * L)(*stats)
     thr_a = (C.c_double * len(thr))(*thr)
     bits_a = (C.c_uint8 * len(bits))(*bits)
     assert len(bits) == len(thr) + 1
-    cfg = DecideCfg(alpha, tau, phi, eps, v_offset, r_mode, len(thr), thr_a, bits_a)
+    cfg = DecideCfg(alpha, tau, phi, eps, v_offset, r_mode, len(thr), drop, 0, thr_a, bits_a)
     bm = np.empty(L, np.uint8)
     bv = np.empty(L, np.uint8)
     sc = np.empty(L, np.float64)

@@ -15,6 +15,7 @@ _LIB_PATH = os.environ.get("STQ_LIBRARY", os.path.join(_PKG, "libstq.so"))  # ov
 
 STQ_FLAG_STATS = 1
 STQ_DECIDE_R_ALG1 = 1
+STQ_DECIDE_NO_DUAL, STQ_DECIDE_NO_TEMPORAL, STQ_DECIDE_NO_SPATIAL = 2, 4, 8
 
 
 class StqError(RuntimeError):
@@ -68,7 +69,7 @@ class Codes(C.Structure):
 
 
 EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_stats",
-           "stq_repack", "stq_repack_many", "stq_decide", "stq_table", "stq_strerror"]
+           "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_table", "stq_strerror"]
 
 _lib = None
 
@@ -98,6 +99,7 @@ def load_library():
     L.stq_repack_many.argtypes = [vp, C.POINTER(RepackJob), u32, u32, vp]
     L.stq_decide.argtypes = [C.POINTER(DecideState), C.POINTER(LayerStats), u32, C.POINTER(DecideCfg), u32,
                              C.POINTER(Bits), C.POINTER(C.c_double)]
+    L.stq_decide_due.argtypes = [u32, u32]
     L.stq_table.argtypes = [C.c_int, u32, C.POINTER(C.c_float), u32]
     for name in EXPORTS[:-1]:
         getattr(L, name).restype = C.c_int
@@ -151,6 +153,10 @@ def make_plan(plan: Sequence) -> "C.Array":
     for a, p in zip(arr, plan):
         a.m_bits, a.v_bits = int(p[0]), int(p[1])
     return arr
+
+
+def decide_due(step: int, update_every: int) -> bool:
+    return bool(load_library().stq_decide_due(step, update_every))
 
 
 def decide(ema: DecideState, stats, step: int, *, alpha=0.1, tau=1000.0, phi=7.2, eps=1e-12, v_offset=0.0,

@@ -18,6 +18,10 @@ uint8_t map_width(double score, const stq_decide_cfg* cfg) {
 
 }  // namespace
 
+extern "C" int stq_decide_due(uint32_t step, uint32_t update_every) {
+  return ((update_every != 0 && step % update_every == 0) || step < 5) ? 1 : 0;
+}
+
 extern "C" int stq_decide(stq_decide_state* ema, const stq_layer_stats* stats, uint32_t n,
                           const stq_decide_cfg* cfg, uint32_t step, stq_bits* plan_out,
                           double* score_out) {
@@ -57,9 +61,11 @@ extern "C" int stq_decide(stq_decide_state* ema, const stq_layer_stats* stats, u
 
   // pass 2: score and Map
   for (uint32_t l = 0; l < n; ++l) {
-    const double score = cfg->phi + std::log2(fac[3 * l + 1] / (ema->r_ema + cfg->eps)) +
-                         std::log2(fac[3 * l] / (ema->n_ema + cfg->eps)) + log_s +
-                         std::log2(fac[3 * l + 2] / (ema->v_ema + cfg->eps));
+    double score = cfg->phi;
+    if (!(cfg->flags & STQ_DECIDE_NO_DUAL))
+      score += std::log2(fac[3 * l + 1] / (ema->r_ema + cfg->eps)) + std::log2(fac[3 * l] / (ema->n_ema + cfg->eps));
+    if (!(cfg->flags & STQ_DECIDE_NO_TEMPORAL)) score += log_s;
+    if (!(cfg->flags & STQ_DECIDE_NO_SPATIAL)) score += std::log2(fac[3 * l + 2] / (ema->v_ema + cfg->eps));
     if (score_out) score_out[l] = score;
     plan_out[l].m_bits = map_width(score, cfg);
     plan_out[l].v_bits = map_width(score + cfg->v_offset, cfg);

@@ -104,10 +104,12 @@ def test_decide_matches_oracle(lib, oracle):
             s = oracle.Stats()
             s.count, s.g_sum, s.g_abs_sum, s.g_sq_sum = g.size, g.sum(), np.abs(g).sum(), (g * g).sum()
             st_or.append(s)
-        for flags in (0, stq.STQ_DECIDE_R_ALG1):
+        for flags in (0, stq.STQ_DECIDE_R_ALG1, binding.STQ_DECIDE_NO_DUAL, binding.STQ_DECIDE_NO_TEMPORAL,
+                      binding.STQ_DECIDE_NO_SPATIAL | stq.STQ_DECIDE_R_ALG1, 14):
             a, b = binding.DecideState(e_lib.n_ema, e_lib.r_ema, e_lib.v_ema), oracle.Ema(e_or.n_ema, e_or.r_ema, e_or.v_ema)
             plan, sc = stq.decide(a, st_lib, step, alpha=0.3, tau=40.0, v_offset=-1.0, flags=flags, **ladder)
-            bm, bv, sc_o = oracle.decide(b, st_or, step, alpha=0.3, tau=40.0, v_offset=-1.0, r_mode=flags, **ladder)
+            bm, bv, sc_o = oracle.decide(b, st_or, step, alpha=0.3, tau=40.0, v_offset=-1.0, r_mode=flags & 1,
+                                         drop=flags >> 1, **ladder)
             np.testing.assert_allclose(sc, sc_o, rtol=0, atol=1e-9)
             thr = np.array(ladder["thr"])
             for l in range(L):
@@ -119,6 +121,12 @@ def test_decide_matches_oracle(lib, oracle):
         assert abs(e_lib.n_ema - e_or.n_ema) <= 1e-15 * abs(e_or.n_ema)
         assert abs(e_lib.r_ema - e_or.r_ema) <= 1e-15 * abs(e_or.r_ema)
         assert abs(e_lib.v_ema - e_or.v_ema) <= 1e-15 * abs(e_or.v_ema)
+
+
+def test_decide_due_matches_oracle(lib, oracle):
+    for U in (0, 1, 7, 50):
+        for t in range(1, 120):
+            assert binding.decide_due(t, U) == oracle.decide_due(t, U)
 
 
 def test_decide_paper_defaults(lib):

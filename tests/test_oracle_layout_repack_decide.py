@@ -188,6 +188,34 @@ def test_score_terms_and_map(oracle):
     assert abs(sc1[0] - want) < 1e-9
 
 
+def test_ablations_drop_exactly_their_terms(oracle):
+    # the component study's variants: each removes its own terms of the score and nothing else
+    rng = np.random.default_rng(31)
+    g1 = rng.standard_normal(4000) * 2e-3
+    g2 = rng.standard_normal(4000) * 5e-4 * np.exp(0.5 * rng.standard_normal(4000))
+    stats = [make_stats(oracle, g1), make_stats(oracle, g2)]
+    t, tau = 30, 20.0
+    full = oracle.decide(oracle.Ema(0, 0, 0), stats, t, alpha=1.0, tau=tau, eps=0.0)[2]
+    n = [np.sqrt(np.mean(g * g)) for g in (g1, g2)]
+    r = [np.std(np.abs(g)) / np.mean(np.abs(g)) for g in (g1, g2)]
+    v = [np.mean(g * g) for g in (g1, g2)]
+    dual = [math.log2(r[l] / np.mean(r)) + math.log2(n[l] / np.mean(n)) for l in range(2)]
+    temporal = math.log2(1.0 + 1.0 / math.cosh(t / tau))
+    spatial = [math.log2(v[l] / np.mean(v)) for l in range(2)]
+    for drop, gone in ((1, dual), (2, [temporal] * 2), (4, spatial), (7, [dual[l] + temporal + spatial[l] for l in range(2)])):
+        sc = oracle.decide(oracle.Ema(0, 0, 0), stats, t, alpha=1.0, tau=tau, eps=0.0, drop=drop)[2]
+        for l in range(2):
+            assert abs((full[l] - sc[l]) - gone[l]) < 1e-9, (drop, l)
+    assert abs(oracle.decide(oracle.Ema(0, 0, 0), stats, t, alpha=1.0, tau=tau, eps=0.0, drop=7)[2][0] - 7.2) < 1e-12
+
+
+def test_decision_cadence(oracle):
+    # Algorithm 1: the decision runs when t mod U = 0 or t < 5
+    due = [t for t in range(1, 41) if oracle.decide_due(t, 10)]
+    assert due == [1, 2, 3, 4, 10, 20, 30, 40]
+    assert [t for t in range(1, 12) if oracle.decide_due(t, 0)] == [1, 2, 3, 4]
+
+
 def test_ema_recurrence_and_zero_init_bias(oracle):
     # Eq. 4 with EMAs initialised at 0 (Alg. 1): after one decision the EMA is alpha*mean, so every
     # ratio is 1/alpha and the score of an average layer is Phi + 3*log2(1/alpha) + log2(S)
