@@ -29,6 +29,10 @@
  *            All levels and thresholds are entries of ONE table
  *            G[j] = fl32(2^(-j/32)): level k of width b is G[k << (9-b)], threshold
  *            k is G[(2k+1) << (8-b)].  Decisions are exact fp32 compares.
+ *   widths 16, 32: the two wide members of the paper's width set B = {4, 8, 16, 32} are not
+ *            quantized block-wise: at 32 bits a state is kept as the fp32 value itself, at 16
+ *            bits as its bfloat16 rounding (round to nearest even; bfloat16 rather than
+ *            half precision because second moments reach 1e-13 and below).  No scales.
  *   tiny blocks: a block whose max is below the smallest normal fp32 (2^-126) is
  *            stored as an all-zero block (scale 0), so 1/s never overflows.
  *   arithmetic: IEEE binary32, round to nearest even, every operation rounded on
@@ -161,10 +165,22 @@ static float bf16_to_f32(uint16_t h) {
  *           codes arrays hold one byte per element, so they are reused in place
  *   st    : if non-NULL, receives the statistics of this tensor for this step
  */
-void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint64_t numel,
-                            uint8_t* um, float* sm, uint8_t* cv, float* sv,
-                            int bm_old, int bv_old, int bm, int bv, int K,
-                            const stq_oracle_hparams* hp, stq_oracle_stats* st) {
+/* value kept for a state of width 16 or 32 */
+float stq_oracle_wide_value(float x, int b) {
+  if (b == 32) return x;
+  uint32_t u; memcpy(&u, &x, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);   /* bfloat16: round to nearest, ties to even */
+  u &= 0xFFFF0000u;
+  float y; memcpy(&y, &u, 4);
+  return y;
+}
+
+/* As stq_oracle_step_widths; states of width 16 or 32 live in mwide / vwide (one float per
+ * element: the stored value itself), their codes and scales are neither read nor written. */
+void stq_oracle_step_wide(float* param, const void* grad, int grad_bf16, uint64_t numel,
+                          uint8_t* um, float* sm, uint8_t* cv, float* sv, float* mwide, float* vwide,
+                          int bm_old, int bv_old, int bm, int bv, int K,
+                          const stq_oracle_hparams* hp, stq_oracle_stats* st) {
   const float beta1 = hp->beta1, beta2 = hp->beta2;
   const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
   const float decay = 1.0f - hp->lr * hp->weight_decay;
@@ -188,8 +204,8 @@ void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint6
        where m_{t-1}, v_{t-1} are the stored (quantized) states */
     for (int i = 0; i < n; ++i) {
       g[i] = grad_bf16 ? bf16_to_f32(((const uint16_t*)grad)[lo + i]) : ((const float*)grad)[lo + i];
-      float mh = sm[j] * stq_oracle_R(bm_old, um[lo + i]);
-      float vh = sv[j] * stq_oracle_L(bv_old, cv[lo + i]);
+      float mh = (bm_old >= 16) ? mwide[lo + i] : sm[j] * stq_oracle_R(bm_old, um[lo + i]);
+      float vh = (bv_old >= 16) ? vwide[lo + i] : sv[j] * stq_oracle_L(bv_old, cv[lo + i]);
       float a = beta1 * mh, c = omb1 * g[i];
       m[i] = a + c;
       float gg = g[i] * g[i];
@@ -198,15 +214,16 @@ void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint6
     }
 
     /* \hat m_t = Quantize(m_t, 'linear'), \hat v_t = Quantize(v_t, 'log') */
-    float s_m = stq_oracle_quant_linear_block(m, n, bm, um + lo);
-    float s_v = stq_oracle_quant_log_block(v, n, bv, cv + lo);
-    sm[j] = s_m;
-    sv[j] = s_v;
+    float s_m = 0.0f, s_v = 0.0f;
+    if (bm < 16) { s_m = stq_oracle_quant_linear_block(m, n, bm, um + lo); sm[j] = s_m; }
+    else for (int i = 0; i < n; ++i) mwide[lo + i] = stq_oracle_wide_value(m[i], bm);
+    if (bv < 16) { s_v = stq_oracle_quant_log_block(v, n, bv, cv + lo); sv[j] = s_v; }
+    else for (int i = 0; i < n; ++i) vwide[lo + i] = stq_oracle_wide_value(v[i], bv);
 
     /* bias correction of the quantized moments and the parameter update */
     for (int i = 0; i < n; ++i) {
-      float mq = s_m * stq_oracle_R(bm, um[lo + i]);
-      float vq = s_v * stq_oracle_L(bv, cv[lo + i]);
+      float mq = (bm >= 16) ? mwide[lo + i] : s_m * stq_oracle_R(bm, um[lo + i]);
+      float vq = (bv >= 16) ? vwide[lo + i] : s_v * stq_oracle_L(bv, cv[lo + i]);
       float mt = mq * ibc1;
       float vt = vq * ibc2;
       float den = sqrtf(vt) + eps;
@@ -229,6 +246,14 @@ void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint6
     }
   }
   free(m); free(v); free(g);
+}
+
+/* The step between quantized widths (2..8). */
+void stq_oracle_step_widths(float* param, const void* grad, int grad_bf16, uint64_t numel,
+                            uint8_t* um, float* sm, uint8_t* cv, float* sv,
+                            int bm_old, int bv_old, int bm, int bv, int K,
+                            const stq_oracle_hparams* hp, stq_oracle_stats* st) {
+  stq_oracle_step_wide(param, grad, grad_bf16, numel, um, sm, cv, sv, NULL, NULL, bm_old, bv_old, bm, bv, K, hp, st);
 }
 
 /* The step with unchanged widths. */
@@ -289,6 +314,37 @@ void stq_oracle_unpack(const uint32_t* words, uint64_t numel, int b, uint8_t* co
       c |= ((words[w] >> (bit % 32)) & 1u) << k;
     }
     codes[idx] = (uint8_t)c;
+  }
+}
+
+/* States of width 16 or 32 use the same tile format with 16- or 32-bit "codes": the fp32 bit
+ * pattern, or its upper half for bfloat16. */
+void stq_oracle_pack_wide(const float* vals, uint64_t numel, int b, uint32_t* words) {
+  uint64_t nw = stq_oracle_code_words(numel, b);
+  memset(words, 0, nw * 4);
+  for (uint64_t idx = 0; idx < numel; ++idx) {
+    uint64_t tile = idx / TILE;
+    uint32_t r = (uint32_t)(idx % TILE);
+    uint32_t i = r / 256, j = (r % 256) / 4, e = r % 4;
+    uint32_t n = 4 * i + e;
+    uint32_t u; memcpy(&u, &vals[idx], 4);
+    uint32_t code = (b == 32) ? u : (u >> 16);
+    uint32_t bit = n * (uint32_t)b;
+    uint64_t w = tile * 64u * (uint64_t)b + (uint64_t)(bit / 32) * 64u + j;
+    words[w] |= code << (bit % 32);   /* 16 | 32: a code never straddles a word */
+  }
+}
+
+void stq_oracle_unpack_wide(const uint32_t* words, uint64_t numel, int b, float* vals) {
+  for (uint64_t idx = 0; idx < numel; ++idx) {
+    uint64_t tile = idx / TILE;
+    uint32_t r = (uint32_t)(idx % TILE);
+    uint32_t i = r / 256, j = (r % 256) / 4, e = r % 4;
+    uint32_t n = 4 * i + e;
+    uint32_t bit = n * (uint32_t)b;
+    uint64_t w = tile * 64u * (uint64_t)b + (uint64_t)(bit / 32) * 64u + j;
+    uint32_t u = (b == 32) ? words[w] : ((words[w] >> (bit % 32)) & 0xFFFFu) << 16;
+    memcpy(&vals[idx], &u, 4);
   }
 }
 

@@ -88,6 +88,16 @@ def lib():
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                              C.POINTER(HParams), C.POINTER(Stats)]
+        L.stq_oracle_step_wide.restype = None
+        L.stq_oracle_step_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.POINTER(HParams), C.POINTER(Stats)]
+        L.stq_oracle_wide_value.restype = C.c_float
+        L.stq_oracle_wide_value.argtypes = [C.c_float, C.c_int]
+        for f in (L.stq_oracle_pack_wide, L.stq_oracle_unpack_wide):
+            f.restype = None
+            f.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_void_p]
         L.stq_oracle_code_words.restype = C.c_uint64
         L.stq_oracle_code_words.argtypes = [C.c_uint64, C.c_int]
         L.stq_oracle_pack.restype = None
@@ -172,6 +182,8 @@ class State:
     sm: np.ndarray = field(default=None)
     cv: np.ndarray = field(default=None)
     sv: np.ndarray = field(default=None)
+    mw: np.ndarray = field(default=None)   # stored values of a first moment kept at 16 or 32 bits
+    vw: np.ndarray = field(default=None)   # ... of a second moment
 
     @property
     def nblocks(self):
@@ -181,19 +193,25 @@ class State:
     def zeros(numel: int, K: int, bm: int, bv: int) -> "State":
         """Alg. 1 initial state m_0 = v_0 = 0: linear zero code is qmax, log blocks have scale 0."""
         nb = (numel + K - 1) // K
-        qmax = (1 << (bm - 1)) - 1
+        qmax = (1 << (bm - 1)) - 1 if bm < 16 else 0
         return State(numel, K, bm, bv,
                      um=np.full(numel, qmax, np.uint8), sm=np.zeros(nb, np.float32),
-                     cv=np.zeros(numel, np.uint8), sv=np.zeros(nb, np.float32))
+                     cv=np.zeros(numel, np.uint8), sv=np.zeros(nb, np.float32),
+                     mw=np.zeros(numel, np.float32) if bm >= 16 else None,
+                     vw=np.zeros(numel, np.float32) if bv >= 16 else None)
 
     def copy(self):
         return State(self.numel, self.K, self.bm, self.bv, self.um.copy(), self.sm.copy(),
-                     self.cv.copy(), self.sv.copy())
+                     self.cv.copy(), self.sv.copy(),
+                     None if self.mw is None else self.mw.copy(), None if self.vw is None else self.vw.copy())
 
 
 def step(param: np.ndarray, grad: np.ndarray, st: State, *, lr, beta1, beta2, eps, weight_decay, t,
          want_stats: bool = False):
     """In-place Adam step of one tensor.  grad is float32, or uint16 holding bf16 bit patterns."""
+    if st.bm >= 16 or st.bv >= 16:
+        return step_transition(param, grad, st, st.bm, st.bv, lr=lr, beta1=beta1, beta2=beta2, eps=eps,
+                               weight_decay=weight_decay, t=t, want_stats=want_stats)
     _chk(param, np.float32)
     assert param.size == st.numel and grad.size == st.numel
     bf16 = grad.dtype == np.uint16
@@ -220,9 +238,14 @@ def step_transition(param: np.ndarray, grad: np.ndarray, st: State, bm_new: int,
     assert grad.flags.c_contiguous
     hp = HParams(lr, beta1, beta2, eps, weight_decay, t)
     stats = Stats() if want_stats else None
-    lib().stq_oracle_step_widths(_p(param), _p(grad), int(bf16), st.numel, _p(st.um), _p(st.sm), _p(st.cv),
-                                 _p(st.sv), st.bm, st.bv, bm_new, bv_new, st.K, C.byref(hp),
-                                 C.byref(stats) if want_stats else None)
+    if max(st.bm, bm_new) >= 16 and st.mw is None:
+        st.mw = np.zeros(st.numel, np.float32)
+    if max(st.bv, bv_new) >= 16 and st.vw is None:
+        st.vw = np.zeros(st.numel, np.float32)
+    lib().stq_oracle_step_wide(_p(param), _p(grad), int(bf16), st.numel, _p(st.um), _p(st.sm), _p(st.cv), _p(st.sv),
+                               _p(st.mw) if st.mw is not None else None, _p(st.vw) if st.vw is not None else None,
+                               st.bm, st.bv, bm_new, bv_new, st.K, C.byref(hp),
+                               C.byref(stats) if want_stats else None)
     st.bm, st.bv = bm_new, bv_new
     return stats
 
@@ -237,6 +260,26 @@ def pack(codes: np.ndarray, b: int) -> np.ndarray:
     w = np.empty(code_words(codes.size, b), np.uint32)
     lib().stq_oracle_pack(_p(codes), codes.size, b, _p(w))
     return w
+
+
+def pack_wide(vals: np.ndarray, b: int) -> np.ndarray:
+    """Storage words of a state kept at 16 or 32 bits."""
+    vals = _chk(np.ascontiguousarray(vals, dtype=np.float32), np.float32)
+    w = np.empty(code_words(vals.size, b), np.uint32)
+    lib().stq_oracle_pack_wide(_p(vals), vals.size, b, _p(w))
+    return w
+
+
+def unpack_wide(words: np.ndarray, numel: int, b: int) -> np.ndarray:
+    words = _chk(np.ascontiguousarray(words, dtype=np.uint32), np.uint32)
+    assert words.size >= code_words(numel, b)
+    v = np.empty(numel, np.float32)
+    lib().stq_oracle_unpack_wide(_p(words), numel, b, _p(v))
+    return v
+
+
+def wide_value(x: float, b: int) -> float:
+    return float(lib().stq_oracle_wide_value(float(np.float32(x)), b))
 
 
 def unpack(words: np.ndarray, numel: int, b: int) -> np.ndarray:
