@@ -45,7 +45,7 @@ enum {
   STQ_OK = 0,
   STQ_EINVAL = -1,  /* null pointer, zero size, count above the context's limit */
   STQ_EALIGN = -2,  /* a device buffer is not aligned as required */
-  STQ_EBITS = -3,   /* a width outside 2..8 */
+  STQ_EBITS = -3,   /* a width outside 2..8 (and, where a stored state is meant, other than 16 or 32) */
   STQ_EBLOCK = -4,  /* block size not 64, 128 or 256 */
   STQ_EDEVICE = -5, /* no such device, or not a gfx950 GPU */
   STQ_EHIP = -6,    /* a HIP runtime call failed */
@@ -65,7 +65,12 @@ typedef struct {
   float* v_scales;    /* device, second-moment block scales                                 */
 } stq_tensor;
 
-/* bit_plan[l]: the widths b_{l,t} of layer l's two states, each in 2..8. */
+/* bit_plan[l]: the widths b_{l,t} of layer l's two states: 2..8 (block-quantized codes), or 16 / 32,
+ * the wide members of the paper's width set {4, 8, 16, 32}: the state is then kept without scales as
+ * the bfloat16 rounding (16) or the fp32 value itself (32) of each element, in the same tile format
+ * with 16- or 32-bit codes (the upper half of the fp32 bit pattern, or all of it).  stq_repack and
+ * stq_repack_many convert between the quantized widths only; a change from or to a wide format
+ * goes through stq_step_transition. */
 typedef struct { uint8_t m_bits, v_bits; } stq_bits;
 
 /* Inputs of Algorithm 1 that the step needs. */

@@ -45,6 +45,9 @@ namespace {
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 int check_bits(uint32_t b) { return (b >= 2 && b <= 8) ? STQ_OK : STQ_EBITS; }
+bool is_wide(uint32_t b) { return b == 16 || b == 32; }
+// widths a state can be stored at: the quantized ones, and 16 (bfloat16) and 32 (fp32) as they are
+int check_bits_stored(uint32_t b) { return (is_wide(b) || check_bits(b) == STQ_OK) ? STQ_OK : STQ_EBITS; }
 
 int lg_block(uint32_t K) {
   switch (K) { case 64: return 6; case 128: return 7; case 256: return 8; default: return -1; }
@@ -67,8 +70,8 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
   out.resize(n);
   uint64_t tiles = 0;
   for (uint32_t l = 0; l < n; ++l) {
-    if (int e = check_bits(plan[l].m_bits)) return e;
-    if (int e = check_bits(plan[l].v_bits)) return e;
+    if (int e = check_bits_stored(plan[l].m_bits)) return e;
+    if (int e = check_bits_stored(plan[l].v_bits)) return e;
     if (t[l].numel == 0) return STQ_EINVAL;
     if (!t[l].m_codes || !t[l].m_scales || !t[l].v_codes || !t[l].v_scales) return STQ_EINVAL;
     if (need_param_grad && (!t[l].param || !t[l].grad)) return STQ_EINVAL;
@@ -122,7 +125,7 @@ int stq_state_bytes(uint64_t numel, uint32_t block, uint32_t bits, uint64_t* cod
                     uint64_t* scale_bytes) {
   if (numel == 0 || (!code_bytes && !scale_bytes)) return STQ_EINVAL;
   if (lg_block(block) < 0) return STQ_EBLOCK;
-  if (int e = check_bits(bits)) return e;
+  if (int e = check_bits_stored(bits)) return e;
   const uint64_t tiles = (numel + kTile - 1) / kTile;
   if (code_bytes) *code_bytes = tiles * 64ull * bits * 4ull;
   if (scale_bytes) *scale_bytes = tiles * (kTile / block) * 4ull;
@@ -260,8 +263,8 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   if (new_plan) {
     for (uint32_t l = 0; l < n; ++l) {
       TensorDesc& d = descs[l];
-      if (int e = check_bits(new_plan[l].m_bits)) return e;
-      if (int e = check_bits(new_plan[l].v_bits)) return e;
+      if (int e = check_bits_stored(new_plan[l].m_bits)) return e;
+      if (int e = check_bits_stored(new_plan[l].v_bits)) return e;
       const uintptr_t span = static_cast<uintptr_t>(d.n_tiles) * 256;
       struct { uint32_t b_old, b_new; uint32_t* cur; void* dst; uint32_t** out; } st[2] = {
           {d.bm, new_plan[l].m_bits, d.m_codes, new_codes[l].m_codes, &d.m_out},
@@ -317,8 +320,13 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   a.lgK = static_cast<uint32_t>(lg_block(hp->block));
 
   const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
+  // kernel variant: 0 in place, 1 widths change, 2 some state is (or becomes) 16 or 32 bits wide
+  int mode = new_plan ? 1 : 0;
+  for (uint32_t l = 0; l < n; ++l)
+    if (is_wide(descs[l].bm) || is_wide(descs[l].bv) || is_wide(descs[l].bm_out) || is_wide(descs[l].bv_out)) mode = 2;
   // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
-  const uint32_t per_cu = want_stats ? (ctx->groups_per_cu < 2 ? ctx->groups_per_cu : 2) : ctx->groups_per_cu;
+  const uint32_t cap_cu = (want_stats || mode == 2) ? 2 : 8;
+  const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
   const uint32_t max_groups = ctx->n_cu * per_cu;
   const uint32_t wpg = kWavesPerGroup;
   const uint32_t need_groups = (total + wpg - 1) / wpg;
@@ -329,7 +337,7 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   const uint64_t per_wave = (total + n_waves - 1) / n_waves;
   a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
-  if (launch_step(a, hp->grad_dtype == 1, want_stats, new_plan != nullptr, groups, stream) != 0) return STQ_EHIP;
+  if (launch_step(a, hp->grad_dtype == 1, want_stats, mode, groups, stream) != 0) return STQ_EHIP;
   if (want_stats)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void zero_kernel(const ZeroArgs a) {
   const uint64_t tile = gid >> 6;
   const uint32_t lane = gid & 63;
   if (tile >= a.n_tiles) return;
-  const uint32_t qmax = (1u << (a.bm - 1)) - 1u;
+  const uint32_t qmax = a.bm >= 16 ? 0u : (1u << (a.bm - 1)) - 1u;  // a 16- or 32-bit state stores +0.0
   for (uint32_t p = 0; p < a.bm; ++p) {
     uint32_t word = 0;
     for (uint32_t n = 0; n < 32; ++n) {

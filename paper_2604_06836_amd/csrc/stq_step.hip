@@ -84,7 +84,7 @@ __device__ __forceinline__ void insert(uint32_t (&w)[3], int n, uint32_t code) {
 // lw holds the lane's words from the one that contains the quarter's first bit; s0 (0, 8, 16 or
 // 24) is the position of that bit in lw[0].
 template <int B>
-__device__ __forceinline__ void unpack_offsets(const uint32_t (&lw)[3], uint32_t s0, uint32_t (&off)[8]) {
+__device__ __forceinline__ void unpack_offsets(const uint32_t* lw, uint32_t s0, uint32_t (&off)[8]) {
   uint32_t w[3];
   w[0] = __builtin_amdgcn_alignbit(lw[1], lw[0], s0);
   w[1] = __builtin_amdgcn_alignbit(lw[2], lw[1], s0);
@@ -331,7 +331,17 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
 // Lane L = (value vL = L>>4, lane group qL = L&15) owns one (state, row) pair's block scale:
 // state = vL>>1, row = 2q + (vL&1), block within the row = qL >> (lgK-4).  A block's owners are
 // 4, 8 or 16 neighbouring lanes of one 16-lane row, so their maxima combine by DPP lane swaps.
-template <bool BF16, bool STATS, bool TAIL, bool XW>
+// bfloat16 rounding (to nearest, ties to even) of a finite float, kept as a float
+__device__ __forceinline__ float bf16_rne(float x) {
+  uint32_t u = f2u(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u2f(u & 0xFFFF0000u);
+}
+
+// MODE 0: widths stay as they are; 1: the launch changes widths (other destination buffers);
+// 2: as 1, and states may have the wide formats: 32 bits = the fp32 value, 16 bits = its bfloat16
+// rounding, stored in the same tile format with 32- or 16-bit codes and without scales.
+template <bool BF16, bool STATS, bool TAIL, int MODE>
 __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t tile, uint32_t q, uint32_t n_valid,
                                                 const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
                                                 uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
@@ -341,6 +351,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   asm volatile("" : "+v"(lane));
   uint32_t lgK = a.lgK;
   asm volatile("" : "+s"(lgK));
+  constexpr bool XW = MODE >= 1, WIDE = MODE == 2;
   const uint32_t bm = d.bm, bv = d.bv;              // widths of the stored codes
   // widths this step writes: the same, unless the launch changes widths (XW)
   const uint32_t bmo = XW ? d.bm_out : bm, bvo = XW ? d.bv_out : bv;
@@ -363,13 +374,14 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 
   // ---- loads for the moment phase --------------------------------------------
   const float sc_old = SC[sbase + sidx];
-  uint32_t lwm[3], lwv[3];
+  constexpr int kMaxWords = WIDE ? 8 : 3;  // a quarter of a wide state is 4 or 8 whole words
+  uint32_t lwm[kMaxWords], lwv[kMaxWords];
   {
-    const uint32_t nwm = (s0m + 8u * bm + 31u) >> 5, nwv = (s0v + 8u * bv + 31u) >> 5;  // 1..3 words
+    const uint32_t nwm = (s0m + 8u * bm + 31u) >> 5, nwv = (s0v + 8u * bv + 31u) >> 5;  // 1..3 words (4, 8 wide)
 #pragma unroll
-    for (int k = 0; k < 3; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? CM[k * 64u + ul] : 0u;
+    for (int k = 0; k < kMaxWords; ++k) lwm[k] = (static_cast<uint32_t>(k) < nwm) ? CM[k * 64u + ul] : 0u;
 #pragma unroll
-    for (int k = 0; k < 3; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? CV[k * 64u + ul] : 0u;
+    for (int k = 0; k < kMaxWords; ++k) lwv[k] = (static_cast<uint32_t>(k) < nwv) ? CV[k * 64u + ul] : 0u;
   }
   float g[8];
   {
@@ -435,19 +447,34 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   float m[8], v[8];
   {
     uint32_t off[8];
-    STQ_SWITCH_BITS(bm, (unpack_offsets<B>(lwm, s0m, off)));
+    float old[8];  // the stored moments m_{t-1}, then v_{t-1}
+    if (WIDE && bm >= 16) {
+#pragma unroll
+      for (int n = 0; n < 8; ++n)
+        old[n] = bm == 32 ? u2f(lwm[n]) : u2f((n & 1) ? (lwm[n >> 1] & 0xFFFF0000u) : (lwm[n >> 1] << 16));
+    } else {
+      STQ_SWITCH_BITS(bm, (unpack_offsets<B>(lwm, s0m, off)));
+#pragma unroll
+      for (int n = 0; n < 8; ++n) old[n] = som[n >> 2] * lds_at(Rreg, off[n]);
+    }
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      const float mh = som[n >> 2] * lds_at(Rreg, off[n]);
-      const float x = a.beta1 * mh, y = a.omb1 * g[n];
+      const float x = a.beta1 * old[n], y = a.omb1 * g[n];
       m[n] = x + y;
     }
-    STQ_SWITCH_BITS(bv, (unpack_offsets<B>(lwv, s0v, off)));
+    if (WIDE && bv >= 16) {
+#pragma unroll
+      for (int n = 0; n < 8; ++n)
+        old[n] = bv == 32 ? u2f(lwv[n]) : u2f((n & 1) ? (lwv[n >> 1] & 0xFFFF0000u) : (lwv[n >> 1] << 16));
+    } else {
+      STQ_SWITCH_BITS(bv, (unpack_offsets<B>(lwv, s0v, off)));
+#pragma unroll
+      for (int n = 0; n < 8; ++n) old[n] = sov[n >> 2] * lds_at(Lreg, off[n]);
+    }
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      const float vh = sov[n >> 2] * lds_at(Lreg, off[n]);
       const float gg = g[n] * g[n];
-      const float x = a.beta2 * vh, y = a.omb2 * gg;
+      const float x = a.beta2 * old[n], y = a.omb2 * gg;
       v[n] = x + y;
     }
   }
@@ -507,16 +534,21 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   }
   SN[qL * 4 + vL] = sc_new;
   SI[qL * 4 + vL] = sc_inv;
-  if ((static_cast<uint32_t>(qL) & ((1u << (lgK - 4)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
+  {
+    // a wide state has no scales: its owners store nothing
+    const bool has_scale = !WIDE || (vL < 2 ? bmo : bvo) < 16;
+    if (has_scale && (static_cast<uint32_t>(qL) & ((1u << (lgK - 4)) - 1u)) == 0u) SC[sbase + sidx] = sc_new;
+  }
   wave_lds_sync();
 
   // ---- table of den = sqrt(vq*ibc2) + eps and 1/den per (row, block, second-moment code) ----
   // Used when a level serves at least four elements: entries = (512/K) << bv_out <= 128.  The table
   // takes the place of XR, whose last readers have finished.
   const UpdateArgs ua = {a.ibc1, a.ibc2, a.eps, a.lr, a.decay};
-  const uint32_t n_entries = (512u >> lgK) << bvo;
+  const bool wide_m = WIDE && bmo >= 16, wide_v = WIDE && bvo >= 16;
+  const uint32_t n_entries = wide_v ? 0xFFFFFFFFu : (512u >> lgK) << bvo;
   const bool use_table = n_entries <= kDenEntries;
-  const uint32_t l_base = 4u << bvo;
+  const uint32_t l_base = wide_v ? 0u : 4u << bvo;
   float2* DEN = reinterpret_cast<float2*>(XR);
   // The short forms of the quotient (and, without a table, of the square root) need every operand
   // in a range where no intermediate underflows or overflows.  The owner lanes check their scales:
@@ -549,9 +581,37 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   } else {
     fast_div = eps_ok && !__any(bad_bits);
   }
+  if (wide_m) fast_div = false;  // a wide first moment is not a multiple of a block scale: no range guarantee
 
   // ---- linear symmetric quantization of m; m is replaced by its quantized value ----
-  {
+  if (wide_m) {
+    float sm_sum = 0.0f, sm_sq = 0.0f, sm_err = 0.0f;
+    uint32_t kept[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const float mq = bmo == 32 ? m[n] : bf16_rne(m[n]);  // pads are 0 and stay 0
+      if (STATS) {
+        const float dd = m[n] - mq;
+        sm_sum += m[n];
+        sm_sq += m[n] * m[n];
+        sm_err += dd * dd;
+      }
+      m[n] = mq;
+      kept[n] = f2u(mq);
+    }
+    if (STATS) {
+      st.add(kLMSum, lane, sm_sum);
+      st.add(kLMSq, lane, sm_sq);
+      st.add(kLMErr, lane, sm_err);
+    }
+    if (bmo == 32) {
+#pragma unroll
+      for (int n = 0; n < 8; ++n) CMO[n * 64u + ul] = kept[n];
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) CMO[k * 64u + ul] = (kept[2 * k] >> 16) | (kept[2 * k + 1] & 0xFFFF0000u);
+    }
+  } else {
     float sn[2], inv[2];
     {
       const float4 a0 = *reinterpret_cast<const float4*>(SN + (lane >> 2) * 4);
@@ -593,7 +653,37 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
-  {
+  if (wide_v) {
+    float sv_sum = 0.0f, sv_sq = 0.0f, sv_err = 0.0f;
+    uint32_t kept[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const float vq = bvo == 32 ? v[n] : bf16_rne(v[n]);
+      if (STATS) {
+        const float dd = v[n] - vq;
+        sv_sum += v[n];
+        sv_sq += v[n] * v[n];
+        sv_err += dd * dd;
+      }
+      kept[n] = f2u(vq);
+      const float mt = m[n] * ua.ibc1;
+      const float vt = vq * ua.ibc2;
+      const float den = __builtin_sqrtf(vt) + ua.eps;
+      theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, ua);
+    }
+    if (STATS) {
+      st.add(kLVSum, lane, sv_sum);
+      st.add(kLVSq, lane, sv_sq);
+      st.add(kLVErr, lane, sv_err);
+    }
+    if (bvo == 32) {
+#pragma unroll
+      for (int n = 0; n < 8; ++n) CVO[n * 64u + ul] = kept[n];
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) CVO[k * 64u + ul] = (kept[2 * k] >> 16) | (kept[2 * k + 1] & 0xFFFF0000u);
+    }
+  } else {
     float sn[2], inv[2];
     {
       const float4 a1 = *reinterpret_cast<const float4*>(SN + (lane >> 2) * 4);
@@ -661,8 +751,8 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // contiguous range: few tensors per wave).
 // The statistics variant needs about 80 more registers and runs one workgroup per CU at a time
 // (a second workgroup of six waves per CU measured slower).
-template <bool BF16, bool STATS, bool XW>
-__global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 4 : 6) void step_kernel(const StepArgs a) {
+template <bool BF16, bool STATS, int MODE>
+__global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + (STATS ? kWavesPerGroup * kStatLdsWords : 0)];
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
@@ -704,11 +794,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 4 : 6) void step_kerne
       if (left >= static_cast<uint64_t>(kTile)) {
 #pragma nounroll
         for (uint32_t q = 0; q < 4; ++q)
-          process_quarter<BF16, STATS, false, XW>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
+          process_quarter<BF16, STATS, false, MODE>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
       } else {
 #pragma nounroll
         for (uint32_t q = 0; q < 4; ++q)
-          process_quarter<BF16, STATS, true, XW>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
+          process_quarter<BF16, STATS, true, MODE>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
                                              carry_v, st);
       }
       if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
@@ -719,23 +809,24 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, STATS ? 4 : 6) void step_kerne
 
 }  // namespace
 
-template <bool XW>
+template <int MODE>
 static void launch_variant(const StepArgs& a, bool grad_bf16, bool want_stats, dim3 grid, dim3 block, hipStream_t s) {
   if (grad_bf16) {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true, XW>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<true, false, XW>), grid, block, 0, s, a);
+    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true, MODE>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<true, false, MODE>), grid, block, 0, s, a);
   } else {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true, XW>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<false, false, XW>), grid, block, 0, s, a);
+    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true, MODE>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<false, false, MODE>), grid, block, 0, s, a);
   }
 }
 
-int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, bool changes_widths, uint32_t groups,
-                void* stream) {
+// mode: 0 in place at unchanged widths, 1 widths change, 2 as 1 with 16- or 32-bit states
+int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, int mode, uint32_t groups, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(groups), block(64 * kWavesPerGroup);
-  if (changes_widths) launch_variant<true>(a, grad_bf16, want_stats, grid, block, s);
-  else launch_variant<false>(a, grad_bf16, want_stats, grid, block, s);
+  if (mode == 2) launch_variant<2>(a, grad_bf16, want_stats, grid, block, s);
+  else if (mode == 1) launch_variant<1>(a, grad_bf16, want_stats, grid, block, s);
+  else launch_variant<0>(a, grad_bf16, want_stats, grid, block, s);
   return static_cast<int>(hipGetLastError());
 }
 

@@ -33,8 +33,10 @@ def oracle_states(oracle, w, plan):
 def assert_tensor_parity(oracle, dm, l, th_ref, st_ref, tag=""):
     th, mw, ms, vw, vs = dm.host_state(l)
     n, K = st_ref.numel, st_ref.K
-    assert np.array_equal(mw, oracle.pack(st_ref.um, st_ref.bm)), f"{tag} m codes tensor {l}"
-    assert np.array_equal(vw, oracle.pack(st_ref.cv, st_ref.bv)), f"{tag} v codes tensor {l}"
+    want_m = oracle.pack_wide(st_ref.mw, st_ref.bm) if st_ref.bm >= 16 else oracle.pack(st_ref.um, st_ref.bm)
+    want_v = oracle.pack_wide(st_ref.vw, st_ref.bv) if st_ref.bv >= 16 else oracle.pack(st_ref.cv, st_ref.bv)
+    assert np.array_equal(mw, want_m), f"{tag} m codes tensor {l}"
+    assert np.array_equal(vw, want_v), f"{tag} v codes tensor {l}"
     assert np.array_equal(ms.view(np.uint32), oracle.pad_scales(st_ref.sm, n, K).view(np.uint32)), f"{tag} m scales {l}"
     assert np.array_equal(vs.view(np.uint32), oracle.pad_scales(st_ref.sv, n, K).view(np.uint32)), f"{tag} v scales {l}"
     err = np.abs(th.astype(np.float64) - th_ref)
@@ -326,6 +328,63 @@ def test_step_transition_argument_checks(ctx):
     assert lib.stq_step_transition(ctx._h, dm.tensors, 1, dm.cplan, None, None, C.byref(hp), None) == -1
     assert call([(5, 4)], dst.data_ptr(), None) == 0
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------- the 16- and 32-bit members of the width set
+WIDTHS = (4, 8, 16, 32)   # the paper's set B
+
+
+@pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64)])
+def test_wide_states_every_combination(oracle, ctx, dtype, K):
+    # 16 tensors, one per (m width, v width) over {4, 8, 16, 32}; ragged sizes; statistics on
+    sizes = [2 * 2048 + 333, 2048, 4096 + 1, 900]
+    tensors = [(f"t{i}", sizes[i % 4] + 3 * i) for i in range(16)]
+    plan = [(WIDTHS[i // 4], WIDTHS[i % 4]) for i in range(16)]
+    w = configs.Workload(98, f"wide-{dtype}-{K}", tensors, K, dtype, 3, "normal_per_tensor")
+    run_both(oracle, ctx, w, plan, 3, stats_steps=(1, 3), tag=w.name)
+
+
+@pytest.mark.parametrize("dtype,K", [("fp32", 256), ("bf16", 128)])
+def test_transitions_among_the_papers_widths(oracle, ctx, dtype, K):
+    # tensor i: first moment WIDTHS[i//4] -> WIDTHS[i%4], second moment WIDTHS[i%4] -> WIDTHS[i//4]
+    sizes = [3 * 2048 + 77, 2048, 4096 + 1, 650]
+    tensors = [(f"t{i}", sizes[i % 4] + 5 * i) for i in range(16)]
+    old = [(WIDTHS[i // 4], WIDTHS[i % 4]) for i in range(16)]
+    new = [(WIDTHS[i % 4], WIDTHS[i // 4]) for i in range(16)]
+    w = configs.Workload(99, f"wtrans-{dtype}-{K}", tensors, K, dtype, 4, "normal_per_tensor")
+    dm = DeviceModel(ctx, w, old)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, old)
+    for t in (1, 2):
+        dm.set_grads(t)
+        dm.step(t)
+        for l in range(16):
+            oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t)
+    dm.set_grads(3)
+    dm.step_transition(3, new, stats=True)
+    torch.cuda.synchronize()
+    gs = dm.ctx.stats(16, dm.stream)
+    for l in range(16):
+        s = oracle.step_transition(th_ref[l], dm.host_grad(l), st_ref[l], *new[l], **w.hparams, t=3, want_stats=True)
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{w.name} tensor {l} {old[l]}->{new[l]}")
+        assert_stats_close(gs[l], s, f"{w.name} tensor {l}")
+    dm.set_grads(4)
+    dm.step(4)
+    torch.cuda.synchronize()
+    for l in range(16):
+        oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=4)
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{w.name} after, tensor {l}")
+
+
+def test_repack_rejects_wide_widths(ctx):
+    n = 4096
+    cb, _ = stq.state_bytes(n, 128, 32)
+    a = torch.zeros(cb // 4, dtype=torch.int32, device="cuda")
+    b = torch.zeros(cb // 4, dtype=torch.int32, device="cuda")
+    lib = stq.load_library()
+    assert lib.stq_repack(ctx._h, n, 128, 0, a.data_ptr(), 16, b.data_ptr(), 8, None) == -3
+    assert lib.stq_repack(ctx._h, n, 128, 1, a.data_ptr(), 8, b.data_ptr(), 32, None) == -3
+    assert stq.state_bytes(n, 128, 16)[0] == 2 * 64 * 16 * 4 and stq.state_bytes(n, 128, 32)[0] == 2 * 64 * 32 * 4
 
 
 # --------------------------------------------------------------------- argument checks

@@ -84,7 +84,7 @@ class DeviceModel:
                 cb, _ = stq.state_bytes(n, self.w.K, b1)
                 spare = self._spare.get((l, state))
                 if spare is None or spare.numel() < cb // 4:
-                    cb_max, _ = stq.state_bytes(n, self.w.K, 8)
+                    cb_max, _ = stq.state_bytes(n, self.w.K, max(8, b1))
                     spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
                 dst = spare[:cb // 4]
                 jobs.append((n, state, cur[l].data_ptr(), b0, dst.data_ptr(), b1))
@@ -122,7 +122,7 @@ class DeviceModel:
                 cb, _ = stq.state_bytes(n, self.w.K, b1)
                 spare = self._spare.get((l, state))
                 if spare is None or spare.numel() < cb // 4:
-                    cb_max, _ = stq.state_bytes(n, self.w.K, 8)
+                    cb_max, _ = stq.state_bytes(n, self.w.K, max(8, b1))
                     spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
                 dst = spare[:cb // 4]
                 ptrs[state] = dst.data_ptr()
