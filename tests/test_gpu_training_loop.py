@@ -2,8 +2,8 @@
 quantized Adam step, the statistics -> decision -> width-change loop of Algorithm 1 running at its
 update cadence, compared with torch's fp32 AdamW on the same data and initial weights.
 
-The paper's ladder {4, 8, 16, 32} is clamped to the widths the library stores (16 and 32 -> 8).
-The statistics of step t come out of step t's kernel, so a new plan takes effect at step t+1.
+Two ladders: the paper's own {4, 8, 16, 32} starting from its initial width 16, and the same clamped
+to the block-quantized widths (16 and 32 -> 8).  The statistics of step t come out of step t's kernel, so a new plan takes effect at step t+1.
 No oracle here: this checks that the pieces work together as an optimizer (loss parity), the
 element-wise parity of every piece is in the other GPU tests.
 """
@@ -50,17 +50,17 @@ def train_fp32(steps):
     return losses
 
 
-def train_quantized(steps, fixed_plan=None):
+def train_quantized(steps, fixed_plan=None, ladder=(4, 8, 8, 8), start=(8, 8)):
     m = make_model(0)
     params = [p for p in m.parameters()]
     L = len(params)
     ctx = stq.Context(0, L)
     stream = torch.cuda.current_stream().cuda_stream
-    plan = [fixed_plan or (8, 8)] * L           # start at the widest stored width
+    plan = [fixed_plan or start] * L
     bufs = []
     for p, (bm, bv) in zip(params, plan):
         n = p.numel()
-        cm, sb = stq.state_bytes(n, K, 8)       # code buffers sized for the widest width, two of each
+        cm, sb = stq.state_bytes(n, K, max(ladder))   # code buffers sized for the widest width, two of each
         bufs.append(dict(m=[torch.empty(cm // 4, dtype=torch.int32, device="cuda") for _ in range(2)],
                          v=[torch.empty(cm // 4, dtype=torch.int32, device="cuda") for _ in range(2)],
                          ms=torch.empty(sb // 4, dtype=torch.float32, device="cuda"),
@@ -101,7 +101,7 @@ def train_quantized(steps, fixed_plan=None):
         pending = None
         if due:
             st = ctx.stats(L, stream)
-            new_plan, _ = stq.decide(ema, st, t, alpha=0.1, tau=100.0, thr=(6.8, 12.0, 24.0), bits=(4, 8, 8, 8))
+            new_plan, _ = stq.decide(ema, st, t, alpha=0.1, tau=100.0, thr=(6.8, 12.0, 24.0), bits=ladder)
             pending = [tuple(int(b) for b in p) for p in new_plan]
         widths.append(np.mean([bm + bv for bm, bv in plan]) / 2)
     torch.cuda.synchronize()
@@ -114,11 +114,14 @@ def test_quantized_adam_trains_like_fp32_adamw():
     ref = train_fp32(steps)
     q8, _ = train_quantized(steps, fixed_plan=(8, 8))
     dyn, widths = train_quantized(steps)
+    paper, pw = train_quantized(steps, ladder=(4, 8, 16, 32), start=(16, 16))   # Algorithm 1's ladder and initial width
     tail = lambda xs: float(np.mean(xs[-50:]))
     assert tail(ref) < 0.35 * float(np.mean(ref[:10]))          # the reference run did learn
     assert tail(q8) <= 1.10 * tail(ref) + 1e-3, (tail(q8), tail(ref))
     assert tail(dyn) <= 1.25 * tail(ref) + 1e-3, (tail(dyn), tail(ref))   # widths fall to 4 bits on this toy problem
+    assert tail(paper) <= 1.25 * tail(ref) + 1e-3, (tail(paper), tail(ref))
     assert min(widths) >= 4 and max(widths) <= 8
-    assert len(set(widths)) > 1                                  # the plan did change during training
-    print("final losses: fp32 %.4f, 8-bit %.4f, dynamic %.4f; mean width %.2f .. %.2f"
-          % (tail(ref), tail(q8), tail(dyn), min(widths), max(widths)))
+    assert len(set(widths)) > 1 and len(set(pw)) > 1             # the plans did change during training
+    assert pw[0] == 16 and min(pw) >= 4 and max(pw) <= 32
+    print("final losses: fp32 %.4f, 8-bit %.4f, dynamic %.4f, paper ladder %.4f; mean width %.2f .. %.2f, paper ladder %.2f .. %.2f"
+          % (tail(ref), tail(q8), tail(dyn), tail(paper), min(widths), max(widths), min(pw), max(pw)))
