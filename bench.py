@@ -104,7 +104,7 @@ def main():
     L = len(w.tensors)
     plan = w.initial_plan()
     ctx = stq.Context(0, max(L, 16))
-    dm = DeviceModel(ctx, w, plan)
+    dm = DeviceModel(ctx, w, plan, spare_width=8 if w.transitions != "none" else 0)
     stream = torch.cuda.current_stream()
 
     # two resident gradient sets, alternated, so consecutive steps see different gradients

@@ -24,7 +24,9 @@ class DeviceModel:
     """All tensors of one workload resident on one GPU."""
 
     def __init__(self, ctx: stq.Context, w: Workload, plan: Sequence[Tuple[int, int]], device="cuda:0",
-                 init_params: bool = True):
+                 init_params: bool = True, spare_width: int = 0):
+        """spare_width > 0: every state gets two code buffers of that width up front (the one in use is a
+        view of the first), so that later width changes allocate nothing."""
         self.ctx, self.w, self.device = ctx, w, torch.device(device)
         self.plan = [tuple(p) for p in plan]
         self.param: List[torch.Tensor] = []
@@ -33,7 +35,8 @@ class DeviceModel:
         self.v_codes: List[torch.Tensor] = []
         self.m_scales: List[torch.Tensor] = []
         self.v_scales: List[torch.Tensor] = []
-        self._spare, self._base = {}, {}   # (tensor, state) -> spare buffer / allocation behind the current view
+        self._spare, self._cw = {}, {}     # (tensor, state) -> spare code buffer; cache of code sizes
+        self.numel = [n for _, n in w.tensors]
         gdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
         for l, (_, n) in enumerate(w.tensors):
             bm, bv = self.plan[l]
@@ -42,8 +45,14 @@ class DeviceModel:
             self.grad.append(torch.zeros(n, dtype=gdt, device=self.device))
             cb_m, sb = stq.state_bytes(n, w.K, bm)
             cb_v, _ = stq.state_bytes(n, w.K, bv)
-            self.m_codes.append(torch.empty(cb_m // 4, dtype=torch.int32, device=self.device))
-            self.v_codes.append(torch.empty(cb_v // 4, dtype=torch.int32, device=self.device))
+            if spare_width:
+                cb_max, _ = stq.state_bytes(n, w.K, spare_width)
+                for state, lst in ((0, self.m_codes), (1, self.v_codes)):
+                    lst.append(torch.empty(cb_max // 4, dtype=torch.int32, device=self.device))
+                    self._spare[(l, state)] = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
+            else:
+                self.m_codes.append(torch.empty(cb_m // 4, dtype=torch.int32, device=self.device))
+                self.v_codes.append(torch.empty(cb_v // 4, dtype=torch.int32, device=self.device))
             self.m_scales.append(torch.empty(sb // 4, dtype=torch.float32, device=self.device))
             self.v_scales.append(torch.empty(sb // 4, dtype=torch.float32, device=self.device))
         self._rebuild()
@@ -69,87 +78,79 @@ class DeviceModel:
     def step(self, t: int, stats: bool = False):
         self.ctx.step(self.tensors, self.cplan, hparams(self.w, t, stats), self.stream)
 
-    def apply_plan(self, new_plan: Sequence[Tuple[int, int]], batched: bool = True, also_patch=()) -> int:
-        """Re-pack every state whose width changed (out of place) and adopt the new plan.
-        Returns the number of re-packed states.  Destination buffers come from a per-state spare
-        (the buffer the state used before, kept at the size of the widest code) so that a loop of
-        transitions allocates nothing once warm.  `also_patch`: further ctypes tensor arrays (other
-        gradient sets of the same model) whose code pointers follow."""
-        jobs, fresh = [], []
+    def _code_words(self, n: int, b: int) -> int:
+        key = (n, b)
+        if key not in self._cw:
+            self._cw[key] = stq.state_bytes(n, self.w.K, b)[0] // 4
+        return self._cw[key]
+
+    def _destinations(self, new_plan):
+        """For every state whose width changes: a destination buffer (the state's spare, or a new one
+        sized for the widest quantized code).  Code buffers may be larger than the state needs."""
+        out = []
         for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
-            n = self.param[l].numel()
+            if bm0 == bm1 and bv0 == bv1:
+                continue
+            n = self.numel[l]
             for state, cur, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
                 if b0 == b1:
                     continue
-                cb, _ = stq.state_bytes(n, self.w.K, b1)
+                need = self._code_words(n, b1)
                 spare = self._spare.get((l, state))
-                if spare is None or spare.numel() < cb // 4:
-                    cb_max, _ = stq.state_bytes(n, self.w.K, max(8, b1))
-                    spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
-                dst = spare[:cb // 4]
-                jobs.append((n, state, cur[l].data_ptr(), b0, dst.data_ptr(), b1))
-                fresh.append((cur, l, state, dst, spare))
-        changed = len(jobs)
+                if spare is None or spare.numel() < need:
+                    spare = torch.empty(self._code_words(n, max(8, b1)), dtype=torch.int32, device=self.device)
+                out.append((l, state, cur, b0, b1, spare, spare.data_ptr()))
+        return out
+
+    def _adopt(self, changes, new_plan, new_cplan, also_patch):
+        arrays = (self.tensors,) + tuple(also_patch)
+        for l, state, cur, b0, b1, dst, ptr in changes:
+            self._spare[(l, state)] = cur[l]
+            cur[l] = dst
+            for arr in arrays:
+                if state == 0:
+                    arr[l].m_codes = ptr
+                else:
+                    arr[l].v_codes = ptr
+        self.plan = [tuple(p) for p in new_plan]
+        self.cplan = new_cplan
+
+    def apply_plan(self, new_plan: Sequence[Tuple[int, int]], batched: bool = True, also_patch=()) -> int:
+        """Re-pack every state whose width changed (out of place) and adopt the new plan.
+        Returns the number of re-packed states.  Destination buffers come from a per-state spare
+        (the buffer the state used before) so that a loop of transitions allocates nothing once warm.
+        `also_patch`: further ctypes tensor arrays (other gradient sets of the same model) whose
+        code pointers follow."""
+        changes = self._destinations(new_plan)
+        jobs = [(self.numel[l], state, cur[l].data_ptr(), b0, ptr, b1) for l, state, cur, b0, b1, dst, ptr in changes]
         if batched and jobs:
             self.ctx.repack_many(jobs, self.w.K, self.stream)
         else:
             for n, state, src, b0, dst, b1 in jobs:
                 self.ctx.repack(n, self.w.K, state, src, b0, dst, b1, self.stream)
-        for cur, l, state, dst, spare in fresh:
-            old = self._base.get((l, state), cur[l])   # whole allocation behind the current view
-            self._spare[(l, state)] = old
-            self._base[(l, state)] = spare
-            cur[l] = dst
-            for arr in (self.tensors,) + tuple(also_patch):
-                if state == 0:
-                    arr[l].m_codes = dst.data_ptr()
-                else:
-                    arr[l].v_codes = dst.data_ptr()
-        self.plan = [tuple(p) for p in new_plan]
-        self.cplan = binding.make_plan(self.plan)
-        return changed
+        self._adopt(changes, new_plan, binding.make_plan(new_plan), also_patch)
+        return len(changes)
 
     def step_transition(self, t: int, new_plan: Sequence[Tuple[int, int]], stats: bool = False, also_patch=()) -> int:
         """One step that reads the states at the current plan and writes them at new_plan
         (stq_step_transition), then adopts the new buffers and plan.  Returns the number of changed states."""
-        dests, fresh = [], []
-        for l, ((bm0, bv0), (bm1, bv1)) in enumerate(zip(self.plan, new_plan)):
-            n = self.param[l].numel()
-            ptrs = [None, None]
-            for state, cur, b0, b1 in ((0, self.m_codes, bm0, bm1), (1, self.v_codes, bv0, bv1)):
-                if b0 == b1:
-                    continue
-                cb, _ = stq.state_bytes(n, self.w.K, b1)
-                spare = self._spare.get((l, state))
-                if spare is None or spare.numel() < cb // 4:
-                    cb_max, _ = stq.state_bytes(n, self.w.K, max(8, b1))
-                    spare = torch.empty(cb_max // 4, dtype=torch.int32, device=self.device)
-                dst = spare[:cb // 4]
-                ptrs[state] = dst.data_ptr()
-                fresh.append((cur, l, state, dst, spare))
-            dests.append(tuple(ptrs))
+        changes = self._destinations(new_plan)
+        dests = [[None, None] for _ in self.plan]
+        for l, state, cur, b0, b1, dst, ptr in changes:
+            dests[l][state] = ptr
         new_cplan = binding.make_plan(new_plan)
         self.ctx.step_transition(self.tensors, self.cplan, new_cplan, dests, hparams(self.w, t, stats), self.stream)
-        for cur, l, state, dst, spare in fresh:
-            old = self._base.get((l, state), cur[l])
-            self._spare[(l, state)] = old
-            self._base[(l, state)] = spare
-            cur[l] = dst
-            for arr in (self.tensors,) + tuple(also_patch):
-                if state == 0:
-                    arr[l].m_codes = dst.data_ptr()
-                else:
-                    arr[l].v_codes = dst.data_ptr()
-        self.plan = [tuple(p) for p in new_plan]
-        self.cplan = new_cplan
-        return len(fresh)
+        self._adopt(changes, new_plan, new_cplan, also_patch)
+        return len(changes)
 
     # ----------------------------------------------------------- host copies
     def host_state(self, l: int):
         """(param, m_code_words, m_scales, v_code_words, v_scales) of tensor l as numpy arrays."""
+        bm, bv = self.plan[l]
+        nm, nv = self._code_words(self.numel[l], bm), self._code_words(self.numel[l], bv)
         return (self.param[l].cpu().numpy(),
-                self.m_codes[l].cpu().numpy().view(np.uint32), self.m_scales[l].cpu().numpy(),
-                self.v_codes[l].cpu().numpy().view(np.uint32), self.v_scales[l].cpu().numpy())
+                self.m_codes[l][:nm].cpu().numpy().view(np.uint32), self.m_scales[l].cpu().numpy(),
+                self.v_codes[l][:nv].cpu().numpy().view(np.uint32), self.v_scales[l].cpu().numpy())
 
     def host_grad(self, l: int) -> np.ndarray:
         g = self.grad[l]
