@@ -327,14 +327,21 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
   const uint32_t cap_cu = (want_stats || mode == 2) ? 2 : 8;
   const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
-  const uint32_t max_groups = ctx->n_cu * per_cu;
   const uint32_t wpg = kWavesPerGroup;
-  const uint32_t need_groups = (total + wpg - 1) / wpg;
-  const uint32_t groups = need_groups < max_groups ? need_groups : max_groups;
-  // tile order (see step_kernel): one contiguous range per wave when statistics are collected,
-  // else interleaved chunks -- single tiles, or four at a time once a wave has many of them
+  const uint32_t max_groups = ctx->n_cu * per_cu;
+  // Units of scheduling (see step_kernel): quarter tiles when whole tiles would leave waves idle and
+  // every width keeps quarters word-aligned (multiples of 4 bits), else tiles.
+  bool quarters = static_cast<uint64_t>(total) < static_cast<uint64_t>(max_groups) * wpg;
+  for (uint32_t l = 0; l < n && quarters; ++l)
+    quarters = ((descs[l].bm | descs[l].bv | descs[l].bm_out | descs[l].bv_out) & 3u) == 0;
+  a.quarter_units = quarters ? 1u : 0u;
+  const uint64_t units = static_cast<uint64_t>(total) << (quarters ? 2 : 0);
+  const uint64_t need_groups = (units + wpg - 1) / wpg;
+  const uint32_t groups = static_cast<uint32_t>(need_groups < max_groups ? need_groups : max_groups);
+  // order of the units (see step_kernel): one contiguous range per wave when statistics are collected,
+  // else interleaved chunks -- single units, or four at a time once a wave has many of them
   const uint64_t n_waves = static_cast<uint64_t>(groups) * wpg;
-  const uint64_t per_wave = (total + n_waves - 1) / n_waves;
+  const uint64_t per_wave = (units + n_waves - 1) / n_waves;
   a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
   if (launch_step(a, hp->grad_dtype == 1, want_stats, mode, groups, stream) != 0) return STQ_EHIP;

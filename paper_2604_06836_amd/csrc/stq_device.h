@@ -42,7 +42,8 @@ struct StepArgs {
   float ibc1, ibc2;        // reciprocal bias corrections 1/(1-beta^t)
   float eps, lr, decay;    // decay = 1 - lr*weight_decay
   uint32_t lgK;            // log2 of the block size: 6, 7 or 8
-  uint32_t chunk;          // consecutive tiles a wave takes at a time, see step_kernel
+  uint32_t chunk;          // consecutive units a wave takes at a time, see step_kernel
+  uint32_t quarter_units;  // 1: a unit is a quarter tile (small launches whose widths keep quarters word-aligned)
 };
 
 struct ZeroArgs {

@@ -763,15 +763,20 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
   uint32_t* ws = lds + kTabWords + wave * kWaveScratch;
   const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * kWaves;
   const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
+  // A unit of scheduling is a tile; in a launch too small to occupy the waves with whole tiles, and
+  // whose widths are all multiples of 4 bits (a quarter's codes then start and end on word
+  // boundaries), it is a quarter tile.
+  const uint32_t qs = a.quarter_units ? 2u : 0u;
+  const uint64_t total_units = static_cast<uint64_t>(a.total_tiles) << qs;
   const uint64_t C = a.chunk;
   uint64_t base = gw * C;
-  if (base >= a.total_tiles) return;
+  if (base >= total_units) return;
 
-  // tensor holding the first tile: last l with tile_begin <= base
+  // tensor holding the first tile: last l with tile_begin <= tile
   uint32_t lo = 0, hi = a.n_tensors - 1;
   while (lo < hi) {
     const uint32_t mid = (lo + hi + 1) >> 1;
-    if (desc_tile_begin(a.desc, mid) <= static_cast<uint32_t>(base)) lo = mid; else hi = mid - 1;
+    if (desc_tile_begin(a.desc, mid) <= static_cast<uint32_t>(base >> qs)) lo = mid; else hi = mid - 1;
   }
   uint32_t l = __builtin_amdgcn_readfirstlane(lo);
   TensorDesc d = load_desc(a.desc, l);
@@ -780,9 +785,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
   st.acc = STATS ? reinterpret_cast<float*>(lds + kLdsWords + wave * kStatLdsWords) : nullptr;
   st.tiles = 0;
   if (STATS) st.clear_all(lane);
-  for (; base < a.total_tiles; base += n_waves * C) {
-    const uint32_t c_end = static_cast<uint32_t>(min(base + C, static_cast<uint64_t>(a.total_tiles)));
-    for (uint32_t t = static_cast<uint32_t>(base); t < c_end; ++t) {
+  for (; base < total_units; base += n_waves * C) {
+    const uint64_t c_end = min(base + C, total_units);
+    for (uint64_t u = base; u < c_end; ++u) {
+      const uint32_t t = static_cast<uint32_t>(u >> qs);
+      const uint32_t q_begin = qs ? static_cast<uint32_t>(u & 3u) : 0u, q_end = qs ? q_begin + 1u : 4u;
       while (t >= d.tile_begin + d.n_tiles) {  // t < total_tiles, so a later tensor holds it
         if (STATS) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
         ++l;
@@ -793,13 +800,13 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
       uint32_t carry_m = 0, carry_v = 0;
       if (left >= static_cast<uint64_t>(kTile)) {
 #pragma nounroll
-        for (uint32_t q = 0; q < 4; ++q)
+        for (uint32_t q = q_begin; q < q_end; ++q)
           process_quarter<BF16, STATS, false, MODE>(d, tile, q, kTile, a, lds, ws, lane, carry_m, carry_v, st);
       } else {
 #pragma nounroll
-        for (uint32_t q = 0; q < 4; ++q)
+        for (uint32_t q = q_begin; q < q_end; ++q)
           process_quarter<BF16, STATS, true, MODE>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
-                                             carry_v, st);
+                                                   carry_v, st);
       }
       if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
     }
