@@ -387,6 +387,50 @@ def test_repack_rejects_wide_widths(ctx):
     assert stq.state_bytes(n, 128, 16)[0] == 2 * 64 * 16 * 4 and stq.state_bytes(n, 128, 32)[0] == 2 * 64 * 32 * 4
 
 
+# ---------------------------------------------------------------- seeded random workloads
+@pytest.mark.parametrize("seed", range(12))
+def test_random_workloads(oracle, ctx, seed):
+    # tensor counts, sizes, block size, gradient type and distribution, widths (quantized and wide),
+    # weight decay and the step at which the widths change are all drawn from the seed
+    rng = np.random.default_rng(1000 + seed)
+    K = int(rng.choice([64, 128, 256]))
+    dtype = str(rng.choice(["fp32", "bf16"]))
+    kind = str(rng.choice(["normal", "normal_per_tensor", "student_t", "normal_per_tensor_step"]))
+    L = int(rng.integers(1, 9))
+    tensors = [(f"t{i}", int(rng.choice([1, 17, 2047, 2048, 2049, 3000, 3 * 2048, 5 * 2048 + 99, 20000])) + int(rng.integers(0, 50)))
+               for i in range(L)]
+    widths = [2, 3, 4, 5, 6, 7, 8] + ([16, 32] if seed % 3 == 0 else [])
+    plan = [(int(rng.choice(widths)), int(rng.choice(widths))) for _ in range(L)]
+    w = configs.Workload(200 + seed, f"random-{seed}", tensors, K, dtype, 5, kind)
+    w.hparams["weight_decay"] = float(rng.choice([0.0, 0.01, 0.1]))
+    w.hparams["lr"] = float(rng.choice([1e-4, 1e-3, 3e-2]))
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    switch_at = int(rng.integers(2, 5))
+    for t in range(1, 6):
+        dm.set_grads(t)
+        want_stats = bool(rng.integers(0, 2))
+        if t == switch_at:
+            new = [(int(rng.choice(widths)), int(rng.choice(widths))) for _ in range(L)]
+            dm.step_transition(t, new, stats=want_stats)
+        else:
+            new = None
+            dm.step(t, stats=want_stats)
+        torch.cuda.synchronize()
+        gs = dm.ctx.stats(L, dm.stream) if want_stats else None
+        for l in range(L):
+            if new is not None:
+                s = oracle.step_transition(th_ref[l], dm.host_grad(l), st_ref[l], *new[l], **w.hparams, t=t, want_stats=True)
+            else:
+                s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{w.name} step {t} tensor {l} {plan[l]}")
+            if want_stats:
+                assert_stats_close(gs[l], s, f"{w.name} step {t} tensor {l}")
+        if new is not None:
+            plan = new
+
+
 # --------------------------------------------------------------------- argument checks
 def test_argument_checks(ctx):
     w = configs.Workload(94, "args", [("a", 4096)], 128, "fp32", 1, "normal")
