@@ -52,15 +52,30 @@ def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2):
 
 def copy_calibration(torch, n=1 << 28, launches=5):
     """dst = src + 1 over 2^28 fp32 elements: each launch reads n*4 bytes and writes n*4 bytes.
-    A profiler's HBM byte counters for this kernel give the factor that scales them to bytes."""
+    A profiler's HBM byte counters for this kernel give the factor that scales them to bytes.
+    Also times three plain streaming kernels of torch, as a measured ceiling for this box."""
     src = torch.zeros(n, dtype=torch.float32, device="cuda:0")
     dst = torch.empty_like(src)
     torch.cuda.synchronize()
     for _ in range(launches):
         torch.add(src, 1.0, out=dst)
     torch.cuda.synchronize()
+
+    def rate(fn, bytes_per_launch, reps=20):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return bytes_per_launch * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     print(json.dumps({"copy_calibration": True, "kernel": "elementwise add", "launches": launches,
-                      "read_bytes_per_launch": n * 4, "write_bytes_per_launch": n * 4}))
+                      "read_bytes_per_launch": n * 4, "write_bytes_per_launch": n * 4,
+                      "streaming_GBps": {"in_place_add (read+write 1 GiB each)": rate(lambda: dst.add_(1.0), 8 * n),
+                                         "out_of_place_add (read 1 GiB, write 1 GiB)": rate(lambda: torch.add(src, 1.0, out=dst), 8 * n),
+                                         "fill (write 1 GiB)": rate(lambda: dst.fill_(0.0), 4 * n)}}))
 
 
 def calibrate_ladder(scores, probs):
