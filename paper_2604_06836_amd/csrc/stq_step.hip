@@ -129,6 +129,8 @@ __device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n
 }
 
 // -------------------------------------------------------------------- statistics
+// (The sums of squares use fused multiply-adds: the fixed operation order binds the Adam
+// arithmetic, not the statistics, which are compared within a tolerance.)
 // Running statistics of one wave, kept in its LDS slice so that they cost no registers between
 // the places that add to them: slot k of lane j is acc[k*64 + j].  Slots 0..8 are fp32 sums of the
 // lane since the last widening, 9..11 running maxima (as bit patterns: all are non-negative)
@@ -299,8 +301,8 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
       if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
       const float d = v[n] - vq;
       sv_sum += v[n];
-      sv_sq += v[n] * v[n];
-      sv_err += d * d;
+      sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
+      sv_err = __builtin_fmaf(d, d, sv_err);
     }
     const float mt = mq[n] * u.ibc1;
     if (TABLE) {
@@ -432,7 +434,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     for (int n = 0; n < 8; ++n) {
       sg_sum += g[n];
       sg_abs += fabsf(g[n]);
-      sg_sq += g[n] * g[n];
+      sg_sq = __builtin_fmaf(g[n], g[n], sg_sq);
       sg_max = fmaxf(sg_max, fabsf(g[n]));
     }
     st.add(kLGSum, lane, sg_sum);
@@ -593,8 +595,8 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (STATS) {
         const float dd = m[n] - mq;
         sm_sum += m[n];
-        sm_sq += m[n] * m[n];
-        sm_err += dd * dd;
+        sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
+        sm_err = __builtin_fmaf(dd, dd, sm_err);
       }
       m[n] = mq;
       kept[n] = f2u(mq);
@@ -639,8 +641,8 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
         if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
         const float dd = m[n] - mq;
         sm_sum += m[n];
-        sm_sq += m[n] * m[n];
-        sm_err += dd * dd;
+        sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
+        sm_err = __builtin_fmaf(dd, dd, sm_err);
       }
       m[n] = mq;
     }
@@ -662,8 +664,8 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (STATS) {
         const float dd = v[n] - vq;
         sv_sum += v[n];
-        sv_sq += v[n] * v[n];
-        sv_err += dd * dd;
+        sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
+        sv_err = __builtin_fmaf(dd, dd, sv_err);
       }
       kept[n] = f2u(vq);
       const float mt = m[n] * ua.ibc1;
