@@ -112,7 +112,7 @@ const char* stq_strerror(int code) {
     case STQ_OK: return "ok";
     case STQ_EINVAL: return "invalid argument";
     case STQ_EALIGN: return "misaligned device buffer";
-    case STQ_EBITS: return "bit-width outside 2..8";
+    case STQ_EBITS: return "bit-width not one of 2..8 (or, for a stored state, 16 or 32)";
     case STQ_EBLOCK: return "block size must be 64, 128 or 256";
     case STQ_EDEVICE: return "device missing or not gfx950";
     case STQ_EHIP: return "HIP runtime error";
