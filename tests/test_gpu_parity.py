@@ -376,6 +376,45 @@ def test_transitions_among_the_papers_widths(oracle, ctx, dtype, K):
         assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{w.name} after, tensor {l}")
 
 
+@pytest.mark.parametrize("b_new", [2, 3, 4, 5, 6, 7, 8])
+def test_second_moments_exactly_on_thresholds_and_levels(oracle, ctx, b_new):
+    # Injected through a 32-bit state: with beta2 = 1/2 and zero gradients the new second moment is exactly
+    # half the stored one, so values 2*T_b[k] land exactly on the decision thresholds of a block of scale 1
+    # (ties must take the larger level), 2*L_b[c] exactly on the levels, and their fp32 neighbours just
+    # beside them.  The first moment does the same for the only exact tie of the linear quantizer (2 bits).
+    K = 64
+    T = np.array(stq.table(3, b_new), np.float32)
+    Lv = np.array(stq.table(2, b_new), np.float32)
+    base = np.concatenate([T, np.nextafter(T, np.float32(2)), np.nextafter(T, np.float32(0)), Lv,
+                           np.nextafter(Lv, np.float32(0))]).astype(np.float32)
+    rows = []
+    for i in range(0, base.size, K - 1):       # every block holds one element at the block maximum 1
+        blk = np.concatenate([[np.float32(1.0)], base[i:i + K - 1]])
+        rows.append(np.pad(blk, (0, K - blk.size), constant_values=np.float32(2.0 ** -20)))
+    v_half = np.concatenate(rows).astype(np.float32)
+    n = v_half.size
+    m_half = np.tile(np.array([1.0, 0.5, -0.5, 0.25, -1.0, 0.0, 0.5, -0.5], np.float32), n // 8 + 1)[:n]
+    w = configs.Workload(120 + b_new, f"ties-{b_new}", [("a", n)], K, "fp32", 1, "normal")
+    w.hparams.update(beta1=0.5, beta2=0.5)
+    dm = DeviceModel(ctx, w, [(32, 32)])
+    st = oracle.State.zeros(n, K, 32, 32)
+    st.mw[:], st.vw[:] = 2 * m_half, 2 * v_half
+    dm.m_codes[0].copy_(torch.from_numpy(oracle.pack_wide(st.mw, 32).view(np.int32)))
+    dm.v_codes[0].copy_(torch.from_numpy(oracle.pack_wide(st.vw, 32).view(np.int32)))
+    dm.grad[0].zero_()
+    th = dm.param[0].cpu().numpy().copy()
+    dm.step_transition(1, [(2, b_new)])
+    torch.cuda.synchronize()
+    oracle.step_transition(th, np.zeros(n, np.float32), st, 2, b_new, **w.hparams, t=1)
+    assert_tensor_parity(oracle, dm, 0, th, st, f"ties b={b_new}")
+    # the cases really are what they claim: an element on threshold k gets level k (code 2^b-1-k)
+    kmax = 2 ** b_new - 1
+    on_thr = st.cv.reshape(-1, K)[0, 1:1 + min(K - 1, T.size)]
+    assert np.array_equal(on_thr, (kmax - np.arange(on_thr.size)).astype(np.uint8))
+    assert np.all(st.sv == 1.0) and np.all(st.sm == 1.0)
+    assert set(st.um.tolist()) <= {0, 1, 2} and np.all(st.um[m_half == 0.5] == 1) and np.all(st.um[m_half == -0.5] == 1)
+
+
 def test_repack_rejects_wide_widths(ctx):
     n = 4096
     cb, _ = stq.state_bytes(n, 128, 32)
