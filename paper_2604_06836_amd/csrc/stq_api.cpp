@@ -16,6 +16,8 @@ using namespace stq;
 
 namespace {
 constexpr int kRing = 4;  // pinned staging slots for descriptor uploads
+constexpr int kDescTables = 4;  // device-resident tensor tables kept: a caller that alternates between a
+                                // few argument sets (two gradient buffers, say) uploads each only once
 }
 
 struct stq_ctx {
@@ -25,7 +27,7 @@ struct stq_ctx {
   uint32_t groups_per_cu = 3;    // resident workgroups per CU the plain step kernel is launched for
   uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
   uint32_t* d_tables = nullptr;
-  TensorDesc* d_desc = nullptr;
+  TensorDesc* d_desc[kDescTables] = {nullptr, nullptr, nullptr, nullptr};
   double* d_stats = nullptr;
   TensorDesc* h_stage[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
   hipEvent_t stage_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
@@ -36,7 +38,8 @@ struct stq_ctx {
   hipEvent_t jobs_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
   int jobs_pos = 0;
   double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
-  std::vector<TensorDesc> uploaded;          // what d_desc currently holds
+  std::vector<TensorDesc> uploaded[kDescTables];  // what each d_desc currently holds
+  int desc_pos = 0;                          // next table to replace
   std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
 };
 
@@ -177,7 +180,8 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
   DeviceGuard g(device);
   bool ok = g.ok;
   ok = ok && hipMalloc(&c->d_tables, img.size() * 4) == hipSuccess;
-  ok = ok && hipMalloc(&c->d_desc, sizeof(TensorDesc) * max_tensors) == hipSuccess;
+  for (int k = 0; k < kDescTables && ok; ++k)
+    ok = ok && hipMalloc(&c->d_desc[k], sizeof(TensorDesc) * max_tensors) == hipSuccess;
   ok = ok && hipMalloc(&c->d_stats, sizeof(double) * kStatSlots * max_tensors) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_stats, sizeof(double) * kStatSlots * max_tensors, hipHostMallocDefault) == hipSuccess;
   for (int k = 0; k < kRing && ok; ++k) {
@@ -215,7 +219,8 @@ int stq_destroy(stq_ctx* c) {
   DeviceGuard g(c->device);
   (void)hipDeviceSynchronize();
   if (c->d_tables) (void)hipFree(c->d_tables);
-  if (c->d_desc) (void)hipFree(c->d_desc);
+  for (int k = 0; k < kDescTables; ++k)
+    if (c->d_desc[k]) (void)hipFree(c->d_desc[k]);
   if (c->d_stats) (void)hipFree(c->d_stats);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->d_luts) (void)hipFree(c->d_luts);
@@ -287,22 +292,28 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   if (!g.ok) return STQ_EHIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  // refresh the device tensor table only when it differs from what is there
-  const bool same = ctx->uploaded.size() == descs.size() &&
-                    std::memcmp(ctx->uploaded.data(), descs.data(), sizeof(TensorDesc) * n) == 0;
-  if (!same) {
+  // upload the tensor table unless one of the device-resident tables already holds it (a table is
+  // replaced in stream order, after the kernels that read it)
+  int table = -1;
+  for (int k = 0; k < kDescTables && table < 0; ++k)
+    if (ctx->uploaded[k].size() == descs.size() &&
+        std::memcmp(ctx->uploaded[k].data(), descs.data(), sizeof(TensorDesc) * n) == 0)
+      table = k;
+  if (table < 0) {
+    table = ctx->desc_pos;
+    ctx->desc_pos = (table + 1) % kDescTables;
     const int k = ctx->ring_pos;
     ctx->ring_pos = (k + 1) % kRing;
     if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
     std::memcpy(ctx->h_stage[k], descs.data(), sizeof(TensorDesc) * n);
-    if (hipMemcpyAsync(ctx->d_desc, ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
+    if (hipMemcpyAsync(ctx->d_desc[table], ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
       return STQ_EHIP;
     if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
-    ctx->uploaded = descs;
+    ctx->uploaded[table] = descs;
   }
 
   StepArgs a;
-  a.desc = ctx->d_desc;
+  a.desc = ctx->d_desc[table];
   a.n_tensors = n;
   a.total_tiles = total;
   a.tables = ctx->d_tables;
