@@ -115,7 +115,9 @@ def main():
         return copy_calibration(torch)
     stq.load_library()  # fails loudly if the HIP library is missing
     w = configs.get_workload(args.workload)
-    steps = args.steps if args.steps is not None else w.steps
+    # default: the configuration's own step count, repeated on the small workloads so that the timed
+    # region lasts tens of milliseconds at least
+    steps = args.steps if args.steps is not None else max(w.steps, min(200, int(2e10 // w.numel)))
     L = len(w.tensors)
     plan = w.initial_plan()
     ctx = stq.Context(0, max(L, 16))
