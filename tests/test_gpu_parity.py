@@ -426,6 +426,32 @@ def test_repack_rejects_wide_widths(ctx):
     assert stq.state_bytes(n, 128, 16)[0] == 2 * 64 * 16 * 4 and stq.state_bytes(n, 128, 32)[0] == 2 * 64 * 32 * 4
 
 
+def test_many_small_tensors_in_one_launch(oracle):
+    # 1500 tensors of 1..5000 elements: every wave walks over many tensor boundaries and ragged tiles
+    rng = np.random.default_rng(77)
+    L = 1500
+    tensors = [(f"t{i}", int(rng.integers(1, 5001))) for i in range(L)]
+    plan = [(int(rng.integers(2, 9)), int(rng.integers(2, 9))) for _ in range(L)]
+    w = configs.Workload(130, "many", tensors, 128, "bf16", 2, "normal_per_tensor")
+    c = stq.Context(0, L)
+    dm = DeviceModel(c, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    for t in (1, 2):
+        dm.set_grads(t)
+        dm.step(t, stats=(t == 2))
+        torch.cuda.synchronize()
+        gs = c.stats(L, dm.stream) if t == 2 else None
+        for l in range(L):
+            s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
+            if gs is not None and l % 13 == 0:
+                assert_stats_close(gs[l], s, f"many tensor {l}")
+    for l in range(L):
+        assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"many tensor {l}")
+    assert all(gs[l].count == tensors[l][1] for l in range(L))
+    c.close()
+
+
 # ---------------------------------------------------------------- seeded random workloads
 @pytest.mark.parametrize("seed", range(12))
 def test_random_workloads(oracle, ctx, seed):
