@@ -75,7 +75,8 @@ typedef struct { uint8_t m_bits, v_bits; } stq_bits;
 
 /* Inputs of Algorithm 1 that the step needs. */
 typedef struct {
-  float lr, beta1, beta2, eps, weight_decay; /* eta, beta1, beta2, epsilon, lambda        */
+  float lr, beta1, beta2, eps, weight_decay; /* eta >= 0, 0 <= beta1, beta2 < 1, epsilon > 0, lambda; all
+                                                finite, else STQ_EINVAL                      */
   uint32_t step;       /* t >= 1, used for the bias corrections 1 - beta^t                */
   uint32_t block;      /* block size K: 64, 128 or 256                                    */
   uint32_t grad_dtype; /* 0 = fp32, 1 = bf16                                              */

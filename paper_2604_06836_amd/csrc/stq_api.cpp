@@ -262,6 +262,10 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
               const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
   if (!hp) return STQ_EINVAL;
   if (hp->step == 0 || hp->grad_dtype > 1) return STQ_EINVAL;
+  // Adam's own preconditions: finite lr >= 0 and weight decay, 0 <= beta < 1, finite eps > 0
+  if (!(hp->lr >= 0.0f) || !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay)) return STQ_EINVAL;
+  if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f)) return STQ_EINVAL;
+  if (!(hp->eps > 0.0f) || !std::isfinite(hp->eps)) return STQ_EINVAL;
   std::vector<TensorDesc> descs;
   uint32_t total = 0;
   if (int e = build_descs(ctx, tensors, n, plan, hp->block, true, descs, &total)) return e;

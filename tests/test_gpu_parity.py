@@ -513,6 +513,11 @@ def test_argument_checks(ctx):
     assert call(hp=bad) == -4
     bad = hparams(w, 0)
     assert call(hp=bad) == -1
+    for field, value in (("eps", 0.0), ("eps", float("nan")), ("beta1", 1.0), ("beta2", -0.1), ("lr", float("inf")),
+                         ("lr", -1e-3), ("weight_decay", float("nan"))):
+        bad = hparams(w, 1)
+        setattr(bad, field, value)
+        assert call(hp=bad) == -1, field
     assert call(n=0) == -1
     t = binding.make_tensors([dict(param=dm.param[0].data_ptr() + 4, grad=dm.grad[0].data_ptr(), numel=4000,
                                    m_codes=dm.m_codes[0].data_ptr(), m_scales=dm.m_scales[0].data_ptr(),
