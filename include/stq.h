@@ -15,8 +15,11 @@
  *     caller; the library never allocates or frees per call.  "host" pointers
  *     are ordinary process memory.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
- *     stq_zero_state, stq_step and stq_repack are asynchronous on that stream;
- *     stq_stats synchronises it.
+ *     stq_zero_state, stq_step, stq_step_transition, stq_repack and stq_repack_many
+ *     are asynchronous on that stream; stq_stats synchronises it.  stq_step,
+ *     stq_step_transition and stq_repack_many upload a small table from pinned host
+ *     memory (and may wait for an upload four calls earlier to have finished), so
+ *     they cannot be recorded into a HIP graph.
  *   - One context serves one stream at a time.  Calls on one context must not
  *     overlap from several host threads.
  *
@@ -31,6 +34,8 @@
  *   stq_state_bytes() returns both sizes.  Both arrays must be 256-byte aligned.
  *   Values: first moment  m = scale * (u - qmax)/qmax,  qmax = 2^(b-1)-1, u = code;
  *           second moment v = scale * 2^(-(2^b-1-c) * 2^(4-b)),  c = code.
+ *   Widths 16 and 32 (see stq_bits) use the same tile format with 16- or 32-bit codes and
+ *   no scales (the scale arrays must still be passed; they are left untouched).
  */
 #ifndef STQ_H
 #define STQ_H
