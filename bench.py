@@ -92,9 +92,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--transition", choices=("repack", "fused"), default="repack",
+    ap.add_argument("--transition", choices=("repack", "fused", "engine"), default="repack",
                     help="how a new bit plan takes effect: stq_repack_many before the step (the configurations' "
-                         "wording), or inside the step with stq_step_transition")
+                         "wording), inside the step with stq_step_transition, or (workloads that decide every "
+                         "step) the device-resident loop stq_engine_step, which never waits for the GPU")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise kernel of known size (scale reference for HBM counters)")
     args = ap.parse_args()
@@ -142,9 +143,16 @@ def main():
 
     fused = args.transition == "fused"
     pending = None  # fused mode: the plan that the next step adopts
+    if args.transition == "engine" and not decide_every_step:
+        sys.exit("bench.py: --transition engine is for the workloads that decide every step (gpt2-xl)")
+    if args.transition == "engine" and args.warmup < 1:
+        sys.exit("bench.py: --transition engine needs --warmup >= 1 (the first step calibrates the ladder on the host)")
+    engine = None   # engine mode: created after the first step has calibrated the ladder
+    import ctypes
+    grad_ptrs = [(ctypes.c_void_p * L)(*[g.data_ptr() for g in grads[k]]) for k in (0, 1)]
 
     def one_step(t, timed):
-        nonlocal plan, ladder, repacked, pending
+        nonlocal plan, ladder, repacked, pending, engine
         k = t % 2
         dm.grad = grads[k]
         dm.tensors = tensor_sets[k]
@@ -158,6 +166,12 @@ def main():
                     plan = new_plan
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
+        if engine is not None:
+            engine.step(hparams(w, t), 1, grad_ptrs[k], dm.stream)
+            e1.record(stream)
+            if timed:
+                kernel_ms.append((e0, e1))
+            return
         if pending is not None:
             repacked += dm.step_transition(t, pending, stats=decide_every_step, also_patch=(tensor_sets[1 - k],))
             plan, pending = pending, None
@@ -177,6 +191,11 @@ def main():
             else:
                 repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
                 plan = new_plan
+            if args.transition == "engine":
+                # hand the loop over to the device: same ladder, the EMAs as they are now
+                second = [(dm._spare[(l, 0)].data_ptr(), dm._spare[(l, 1)].data_ptr()) for l in range(L)]
+                engine = ctx.engine(dm.tensors, second, dm.cplan, 8, w.K, alpha=0.3, tau=4.0, v_offset=-0.5,
+                                    thr=ladder, bits=w.bits_m, ema=ema, stream=dm.stream)
 
     t = 0
     for _ in range(args.warmup):
@@ -191,6 +210,10 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    if engine is not None:
+        plan = engine.read(dm.stream)["stored"]
+        engine.close()
+        repacked = None  # the host never sees the individual decisions
     n = w.numel
     ms_per_step = dt * 1e3 / steps
     kms = [a.elapsed_time(b) for a, b in kernel_ms]

@@ -207,6 +207,51 @@ int stq_decide(stq_decide_state* ema, const stq_layer_stats* stats, uint32_t n,
  * U = 0 means "only during the first steps". */
 int stq_decide_due(uint32_t step, uint32_t update_every);
 
+/* ---- Device-resident precision loop -------------------------------------------------
+ * Algorithm 1's whole iteration (the layer loop, and every U steps the statistics ->
+ * EMAs -> score -> Map body) with the bit plan, the EMAs and the tensor table living
+ * on the device: stq_engine_step only enqueues kernels, nothing is copied back and the
+ * host never waits.  The decision is the one stq_decide takes (same formulas, fp64,
+ * same order of the sums over the layers; log2 is the device library's); it is made
+ * from the gradients of step t inside that step's kernel and takes effect in step
+ * t+1, which reads each state at its old width and writes it at the new one (the
+ * width-changing step of stq_step_transition). */
+typedef struct stq_engine stq_engine;
+
+/* tensors[l] (host array of n): the parameter, gradient, scale arrays and FIRST code
+ * buffers, holding states at the widths of initial_plan (stq_zero_state, or a restored
+ * checkpoint); second[l]: a SECOND code buffer per state.  Every code buffer must hold
+ * the state at capacity_bits (stq_state_bytes), and capacity_bits must be at least every
+ * width of initial_plan and of cfg->bits; scale arrays are needed even while a state is
+ * 16 or 32 bits wide.  A state lives in one of its two buffers and moves to the other
+ * when its width changes.  cfg->n_thr may not exceed 15; cfg is copied.  The EMAs start
+ * at *ema (zeros if NULL).  The engine keeps the context's device; destroy it before
+ * the context. */
+int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
+                      const stq_codes* second, uint32_t n, const stq_bits* initial_plan,
+                      uint32_t capacity_bits, uint32_t block, const stq_decide_cfg* cfg,
+                      const stq_decide_state* ema, void* hip_stream);
+
+/* Step hp->step of the loop (hp->block must be the engine's; STQ_FLAG_STATS in hp->flags
+ * is ignored: the engine collects statistics exactly when stq_decide_due(hp->step,
+ * update_every) says so, and then runs the decision kernel after the step).  grads: NULL,
+ * or a host array of n device pointers that replace the tensors' gradient buffers from
+ * this step on (read before the call returns).  Steps must be enqueued in order on one
+ * stream. */
+int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
+                    const void* const* grads, void* hip_stream);
+
+/* Copy the loop's state to the host and synchronise the stream (for checkpoints,
+ * logging and tests; not needed to run the loop).  Any output may be NULL.
+ * stored[l]: the widths the states of tensor l are held at now; next[l]: the widths the
+ * next step will write; current[l]: the buffers that hold the states now; score (n
+ * doubles) and *ema: from the last decision. */
+int stq_engine_read(stq_engine* e, stq_bits* stored, stq_bits* next, stq_codes* current,
+                    double* score, stq_decide_state* ema, void* hip_stream);
+
+/* Synchronise the device and free what the engine owns (not the caller's buffers). */
+int stq_engine_destroy(stq_engine* e);
+
 /* The library's own quantizer tables, for inspection (host only, no context):
  *   which 0: G[j] = fl32(2^(-j/32)), j < 511 (bits ignored)
  *   which 1: first-moment values R_b[u], u < 2^b - 1

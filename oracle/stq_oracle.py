@@ -328,3 +328,30 @@ def decide(ema: Ema, stats: list, step_t: int, *, alpha=0.1, tau=1000.0, phi=PAP
     sc = np.empty(L, np.float64)
     lib().stq_oracle_decide(C.byref(ema), arr, L, C.byref(cfg), step_t, _p(bm), _p(bv), _p(sc))
     return bm, bv, sc
+
+
+def loop(params: list, states: list, grads_of_step, steps: int, U: int, hp: dict, decide_kw: dict, ema: Ema = None,
+         first_step: int = 1, next_plan: list = None):
+    """Algorithm 1's iteration over a model of several layers, for steps first_step .. first_step+steps-1:
+    every step runs the layer loop; when the cadence says so (t mod U = 0 or t < 5) the layer statistics
+    of that step's gradients go through the Score Engine and Map.  The statistics are those gathered
+    during the step, so the widths Map returns are the ones the NEXT step writes (it reads the states at
+    the old widths).  params[l], states[l] are updated in place; grads_of_step(t) returns the list of
+    gradient arrays of step t.  next_plan: the widths the first of these steps writes, when an earlier
+    decision is still to take effect (default: the stored widths).  Returns (a list of per-step records
+    (t, plan written in that step, scores or None), the widths the following step would write, the EMAs)."""
+    ema = ema if ema is not None else Ema(0.0, 0.0, 0.0)
+    nxt = list(next_plan) if next_plan is not None else [(st.bm, st.bv) for st in states]
+    log = []
+    for t in range(first_step, first_step + steps):
+        due = decide_due(t, U)
+        grads = grads_of_step(t)
+        stats = []
+        for p, g, st, (bm, bv) in zip(params, grads, states, nxt):
+            stats.append(step_transition(p, g, st, bm, bv, t=t, want_stats=due, **hp))
+        written, scores = list(nxt), None
+        if due:
+            bm, bv, scores = decide(ema, stats, t, **decide_kw)
+            nxt = [(int(a), int(b)) for a, b in zip(bm, bv)]
+        log.append((t, written, scores))
+    return log, nxt, ema

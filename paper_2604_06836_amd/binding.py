@@ -69,7 +69,8 @@ class Codes(C.Structure):
 
 
 EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_stats",
-           "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_table", "stq_strerror"]
+           "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_step",
+           "stq_engine_read", "stq_engine_destroy", "stq_table", "stq_strerror"]
 
 _lib = None
 
@@ -101,6 +102,12 @@ def load_library():
                              C.POINTER(Bits), C.POINTER(C.c_double)]
     L.stq_decide_due.argtypes = [u32, u32]
     L.stq_table.argtypes = [C.c_int, u32, C.POINTER(C.c_float), u32]
+    L.stq_engine_create.argtypes = [vp, C.POINTER(vp), C.POINTER(Tensor), C.POINTER(Codes), u32, C.POINTER(Bits), u32,
+                                    u32, C.POINTER(DecideCfg), C.POINTER(DecideState), vp]
+    L.stq_engine_step.argtypes = [vp, C.POINTER(HParams), u32, C.POINTER(vp), vp]
+    L.stq_engine_read.argtypes = [vp, C.POINTER(Bits), C.POINTER(Bits), C.POINTER(Codes), C.POINTER(C.c_double),
+                                  C.POINTER(DecideState), vp]
+    L.stq_engine_destroy.argtypes = [vp]
     for name in EXPORTS[:-1]:
         getattr(L, name).restype = C.c_int
     L.stq_strerror.argtypes = [C.c_int]
@@ -227,3 +234,60 @@ class Context:
                stream: int = 0):
         _check(self._lib.stq_repack(self._h, numel, block, state, C.c_void_p(src), src_bits,
                                     C.c_void_p(dst), dst_bits, C.c_void_p(stream)), "stq_repack")
+
+    def engine(self, tensors, second, plan, capacity_bits: int, block: int, *, alpha=0.1, tau=1000.0, phi=7.2,
+               eps=1e-12, v_offset=0.0, flags=0, thr=(6.8, 12.0, 24.0), bits=(4, 8, 16, 32),
+               ema: Optional[DecideState] = None, stream: int = 0) -> "Engine":
+        """stq_engine_create.  second: sequence of (m_ptr, v_ptr), the second code buffer of each state."""
+        return Engine(self, tensors, second, plan, capacity_bits, block, alpha=alpha, tau=tau, phi=phi, eps=eps,
+                      v_offset=v_offset, flags=flags, thr=thr, bits=bits, ema=ema, stream=stream)
+
+
+class Engine:
+    """Owns an stq_engine: the device-resident precision loop.  Close it before its Context."""
+
+    def __init__(self, ctx: Context, tensors, second, plan, capacity_bits: int, block: int, *, alpha, tau, phi, eps,
+                 v_offset, flags, thr, bits, ema, stream):
+        if len(bits) != len(thr) + 1:
+            raise ValueError("bits must have len(thr)+1 entries")
+        self._lib, self._ctx, self.n = ctx._lib, ctx, len(tensors)
+        self._h = C.c_void_p()
+        thr_a = (C.c_double * len(thr))(*thr)
+        bits_a = (C.c_uint8 * len(bits))(*bits)
+        cfg = DecideCfg(alpha, tau, phi, eps, v_offset, flags, len(thr), thr_a, bits_a)
+        sec = (Codes * self.n)()
+        for a, (m, v) in zip(sec, second):
+            a.m_codes, a.v_codes = m, v
+        _check(self._lib.stq_engine_create(ctx._h, C.byref(self._h), tensors, sec, self.n, plan, capacity_bits, block,
+                                           C.byref(cfg), C.byref(ema) if ema is not None else None,
+                                           C.c_void_p(stream)), "stq_engine_create")
+
+    def step(self, hp: HParams, update_every: int, grads: Optional[Sequence[int]] = None, stream: int = 0):
+        """grads: None, or the addresses of the n gradient buffers to use from this step on (a ctypes
+        array of c_void_p is passed through as it is)."""
+        if grads is not None and not isinstance(grads, C.Array):
+            grads = (C.c_void_p * self.n)(*grads)
+        _check(self._lib.stq_engine_step(self._h, C.byref(hp), update_every, grads, C.c_void_p(stream)),
+               "stq_engine_step")
+
+    def read(self, stream: int = 0):
+        """stq_engine_read: dict with stored and next plans [(m_bits, v_bits)], current code buffers
+        [(m_ptr, v_ptr)], scores and the EMAs (n_ema, r_ema, v_ema)."""
+        stored, nxt, cur = (Bits * self.n)(), (Bits * self.n)(), (Codes * self.n)()
+        score, ema = (C.c_double * self.n)(), DecideState(0, 0, 0)
+        _check(self._lib.stq_engine_read(self._h, stored, nxt, cur, score, C.byref(ema), C.c_void_p(stream)),
+               "stq_engine_read")
+        return dict(stored=[(p.m_bits, p.v_bits) for p in stored], next=[(p.m_bits, p.v_bits) for p in nxt],
+                    current=[(c.m_codes, c.v_codes) for c in cur], score=list(score),
+                    ema=(ema.n_ema, ema.r_ema, ema.v_ema))
+
+    def close(self):
+        if self._h:
+            self._lib.stq_engine_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

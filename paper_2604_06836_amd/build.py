@@ -21,7 +21,7 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-ffp-contract=off",
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-Wall", "-Wextra", "-Wno-unused-parameter"]
 
-SOURCES = ["stq_step.hip", "stq_kernels.hip", "stq_api.cpp", "stq_tables.cpp", "stq_decide.cpp"]
+SOURCES = ["stq_step.hip", "stq_kernels.hip", "stq_engine.hip", "stq_api.cpp", "stq_tables.cpp", "stq_decide.cpp"]
 
 
 def _compile(src: str) -> str:

@@ -1,70 +1,17 @@
 // Host side of the C ABI declared in include/stq.h: argument checks, the device-resident
 // tensor table, kernel launches, statistics read-back.  Compiled by hipcc (HIP runtime calls).
-#include <hip/hip_runtime.h>
-
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
 
-#include "stq.h"
-#include "stq_device.h"
+#include "stq_host.h"
 #include "stq_tables.h"
 
 using namespace stq;
 
-namespace {
-constexpr int kRing = 4;  // pinned staging slots for descriptor uploads
-constexpr int kDescTables = 4;  // device-resident tensor tables kept: a caller that alternates between a
-                                // few argument sets (two gradient buffers, say) uploads each only once
-}
-
-struct stq_ctx {
-  int device = -1;
-  uint32_t max_tensors = 0;
-  uint32_t n_cu = 0;
-  uint32_t groups_per_cu = 3;    // resident workgroups per CU the plain step kernel is launched for
-  uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
-  uint32_t* d_tables = nullptr;
-  TensorDesc* d_desc[kDescTables] = {nullptr, nullptr, nullptr, nullptr};
-  double* d_stats = nullptr;
-  TensorDesc* h_stage[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
-  hipEvent_t stage_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
-  int ring_pos = 0;
-  uint32_t* d_luts = nullptr;                // every conversion table of the re-pack, kRepackLuts x 256 words
-  RepackJob* d_jobs = nullptr;               // 2 * max_tensors
-  RepackJob* h_jobs[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
-  hipEvent_t jobs_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
-  int jobs_pos = 0;
-  double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
-  std::vector<TensorDesc> uploaded[kDescTables];  // what each d_desc currently holds
-  int desc_pos = 0;                          // next table to replace
-  std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
-};
-
-namespace {
-
-bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
-int check_bits(uint32_t b) { return (b >= 2 && b <= 8) ? STQ_OK : STQ_EBITS; }
-bool is_wide(uint32_t b) { return b == 16 || b == 32; }
-// widths a state can be stored at: the quantized ones, and 16 (bfloat16) and 32 (fp32) as they are
-int check_bits_stored(uint32_t b) { return (is_wide(b) || check_bits(b) == STQ_OK) ? STQ_OK : STQ_EBITS; }
-
-int lg_block(uint32_t K) {
-  switch (K) { case 64: return 6; case 128: return 7; case 256: return 8; default: return -1; }
-}
-
-struct DeviceGuard {  // makes the context's device current for the duration of a call
-  int prev = -1; bool ok = false;
-  explicit DeviceGuard(int dev) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
-    if (prev == dev) prev = -1;
-  }
-  ~DeviceGuard() { if (ok && prev >= 0) (void)hipSetDevice(prev); }
-};
+namespace stq {
 
 int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
                 bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles) {
@@ -106,7 +53,7 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
   return STQ_OK;
 }
 
-}  // namespace
+}  // namespace stq
 
 extern "C" {
 
@@ -255,17 +202,71 @@ int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const st
   return STQ_OK;
 }
 
-namespace {
+}  // extern "C"
 
-// One launch of the step kernel.  new_plan/new_codes are null for the in-place step.
-int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
-              const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
+namespace stq {
+
+int check_hparams(const stq_hparams* hp) {
   if (!hp) return STQ_EINVAL;
   if (hp->step == 0 || hp->grad_dtype > 1) return STQ_EINVAL;
   // Adam's own preconditions: finite lr >= 0 and weight decay, 0 <= beta < 1, finite eps > 0
   if (!(hp->lr >= 0.0f) || !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay)) return STQ_EINVAL;
   if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f)) return STQ_EINVAL;
   if (!(hp->eps > 0.0f) || !std::isfinite(hp->eps)) return STQ_EINVAL;
+  if (lg_block(hp->block) < 0) return STQ_EBLOCK;
+  return STQ_OK;
+}
+
+int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total, double* d_stats,
+                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream) {
+  StepArgs a;
+  a.desc = d_desc;
+  a.n_tensors = n;
+  a.total_tiles = total;
+  a.tables = ctx->d_tables;
+  a.stats = d_stats;
+  a.beta1 = hp->beta1;
+  a.omb1 = 1.0f - hp->beta1;
+  a.beta2 = hp->beta2;
+  a.omb2 = 1.0f - hp->beta2;
+  // reciprocal bias corrections 1/(1 - beta^t): double arithmetic, one rounding to fp32
+  a.ibc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta1), static_cast<double>(hp->step))));
+  a.ibc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta2), static_cast<double>(hp->step))));
+  a.eps = hp->eps;
+  a.lr = hp->lr;
+  a.decay = 1.0f - hp->lr * hp->weight_decay;
+  a.lgK = static_cast<uint32_t>(lg_block(hp->block));
+
+  const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
+  // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
+  const uint32_t cap_cu = (want_stats || mode == 2) ? 2 : 8;
+  const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
+  const uint32_t wpg = kWavesPerGroup;
+  const uint32_t max_groups = ctx->n_cu * per_cu;
+  // Units of scheduling (see step_kernel): quarter tiles when whole tiles would leave waves idle and
+  // every width keeps quarters word-aligned (multiples of 4 bits), else tiles.
+  const bool quarters = quarters_ok && static_cast<uint64_t>(total) < static_cast<uint64_t>(max_groups) * wpg;
+  a.quarter_units = quarters ? 1u : 0u;
+  const uint64_t units = static_cast<uint64_t>(total) << (quarters ? 2 : 0);
+  const uint64_t need_groups = (units + wpg - 1) / wpg;
+  const uint32_t groups = static_cast<uint32_t>(need_groups < max_groups ? need_groups : max_groups);
+  // order of the units (see step_kernel): one contiguous range per wave when statistics are collected,
+  // else interleaved chunks -- single units, or four at a time once a wave has many of them
+  const uint64_t n_waves = static_cast<uint64_t>(groups) * wpg;
+  const uint64_t per_wave = (units + n_waves - 1) / n_waves;
+  a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
+  if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
+  return launch_step(a, hp->grad_dtype == 1, want_stats, mode, groups, stream) == 0 ? STQ_OK : STQ_EHIP;
+}
+
+}  // namespace stq
+
+namespace {
+
+// One launch of the step kernel.  new_plan/new_codes are null for the in-place step.
+int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+              const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
+  if (int e = check_hparams(hp)) return e;
   std::vector<TensorDesc> descs;
   uint32_t total = 0;
   if (int e = build_descs(ctx, tensors, n, plan, hp->block, true, descs, &total)) return e;
@@ -316,56 +317,23 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
     ctx->uploaded[table] = descs;
   }
 
-  StepArgs a;
-  a.desc = ctx->d_desc[table];
-  a.n_tensors = n;
-  a.total_tiles = total;
-  a.tables = ctx->d_tables;
-  a.stats = ctx->d_stats;
-  a.beta1 = hp->beta1;
-  a.omb1 = 1.0f - hp->beta1;
-  a.beta2 = hp->beta2;
-  a.omb2 = 1.0f - hp->beta2;
-  // reciprocal bias corrections 1/(1 - beta^t): double arithmetic, one rounding to fp32
-  a.ibc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta1), static_cast<double>(hp->step))));
-  a.ibc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(hp->beta2), static_cast<double>(hp->step))));
-  a.eps = hp->eps;
-  a.lr = hp->lr;
-  a.decay = 1.0f - hp->lr * hp->weight_decay;
-  a.lgK = static_cast<uint32_t>(lg_block(hp->block));
-
-  const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
   // kernel variant: 0 in place, 1 widths change, 2 some state is (or becomes) 16 or 32 bits wide
   int mode = new_plan ? 1 : 0;
-  for (uint32_t l = 0; l < n; ++l)
-    if (is_wide(descs[l].bm) || is_wide(descs[l].bv) || is_wide(descs[l].bm_out) || is_wide(descs[l].bv_out)) mode = 2;
-  // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
-  const uint32_t cap_cu = (want_stats || mode == 2) ? 2 : 8;
-  const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
-  const uint32_t wpg = kWavesPerGroup;
-  const uint32_t max_groups = ctx->n_cu * per_cu;
-  // Units of scheduling (see step_kernel): quarter tiles when whole tiles would leave waves idle and
-  // every width keeps quarters word-aligned (multiples of 4 bits), else tiles.
-  bool quarters = static_cast<uint64_t>(total) < static_cast<uint64_t>(max_groups) * wpg;
-  for (uint32_t l = 0; l < n && quarters; ++l)
-    quarters = ((descs[l].bm | descs[l].bv | descs[l].bm_out | descs[l].bv_out) & 3u) == 0;
-  a.quarter_units = quarters ? 1u : 0u;
-  const uint64_t units = static_cast<uint64_t>(total) << (quarters ? 2 : 0);
-  const uint64_t need_groups = (units + wpg - 1) / wpg;
-  const uint32_t groups = static_cast<uint32_t>(need_groups < max_groups ? need_groups : max_groups);
-  // order of the units (see step_kernel): one contiguous range per wave when statistics are collected,
-  // else interleaved chunks -- single units, or four at a time once a wave has many of them
-  const uint64_t n_waves = static_cast<uint64_t>(groups) * wpg;
-  const uint64_t per_wave = (units + n_waves - 1) / n_waves;
-  a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
-  if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
-  if (launch_step(a, hp->grad_dtype == 1, want_stats, mode, groups, stream) != 0) return STQ_EHIP;
-  if (want_stats)
+  bool quarters_ok = true;
+  for (uint32_t l = 0; l < n; ++l) {
+    const TensorDesc& d = descs[l];
+    if (is_wide(d.bm) || is_wide(d.bv) || is_wide(d.bm_out) || is_wide(d.bv_out)) mode = 2;
+    quarters_ok = quarters_ok && ((d.bm | d.bv | d.bm_out | d.bv_out) & 3u) == 0;
+  }
+  if (int e = launch_table(ctx, ctx->d_desc[table], n, total, ctx->d_stats, hp, mode, quarters_ok, stream)) return e;
+  if ((hp->flags & STQ_FLAG_STATS) != 0)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;
 }
 
 }  // namespace
+
+extern "C" {
 
 int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
              const stq_hparams* hp, void* stream) {

@@ -1,0 +1,80 @@
+// Host-side internals shared by the sources that implement the C ABI: the context, argument
+// checks, and the one place that configures and launches the step kernel over a device-resident
+// tensor table.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "stq.h"
+#include "stq_device.h"
+
+namespace stq {
+
+constexpr int kRing = 4;        // pinned staging slots for descriptor uploads
+constexpr int kDescTables = 4;  // device-resident tensor tables kept: a caller that alternates between a
+                                // few argument sets (two gradient buffers, say) uploads each only once
+
+}  // namespace stq
+
+struct stq_ctx {
+  int device = -1;
+  uint32_t max_tensors = 0;
+  uint32_t n_cu = 0;
+  uint32_t groups_per_cu = 3;    // resident workgroups per CU the plain step kernel is launched for
+  uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
+  uint32_t* d_tables = nullptr;
+  stq::TensorDesc* d_desc[stq::kDescTables] = {nullptr, nullptr, nullptr, nullptr};
+  double* d_stats = nullptr;
+  stq::TensorDesc* h_stage[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
+  hipEvent_t stage_done[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};
+  int ring_pos = 0;
+  uint32_t* d_luts = nullptr;                // every conversion table of the re-pack, kRepackLuts x 256 words
+  stq::RepackJob* d_jobs = nullptr;          // 2 * max_tensors
+  stq::RepackJob* h_jobs[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
+  hipEvent_t jobs_done[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};
+  int jobs_pos = 0;
+  double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
+  std::vector<stq::TensorDesc> uploaded[stq::kDescTables];  // what each d_desc currently holds
+  int desc_pos = 0;                          // next table to replace
+  std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
+};
+
+namespace stq {
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline int check_bits(uint32_t b) { return (b >= 2 && b <= 8) ? STQ_OK : STQ_EBITS; }
+inline bool is_wide(uint32_t b) { return b == 16 || b == 32; }
+// widths a state can be stored at: the quantized ones, and 16 (bfloat16) and 32 (fp32) as they are
+inline int check_bits_stored(uint32_t b) { return (is_wide(b) || check_bits(b) == STQ_OK) ? STQ_OK : STQ_EBITS; }
+
+inline int lg_block(uint32_t K) {
+  switch (K) { case 64: return 6; case 128: return 7; case 256: return 8; default: return -1; }
+}
+
+struct DeviceGuard {  // makes the context's device current for the duration of a call
+  int prev = -1; bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() { if (ok && prev >= 0) (void)hipSetDevice(prev); }
+};
+
+// Checks the hyper-parameters of a step (Adam's own preconditions).
+int check_hparams(const stq_hparams* hp);
+
+// Fills the descriptors of n tensors at the widths of `plan` (new codes in place) and the launch-wide tile count.
+int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
+                bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles);
+
+// Launches the step kernel over the device-resident table `d_desc` of n tensors / total_tiles tiles.
+// mode: 0 in place, 1 widths change, 2 some state is (or may become) 16 or 32 bits wide.
+// quarters_ok: every width of the launch is a multiple of 4 bits.
+int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total_tiles, double* d_stats,
+                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream);
+
+}  // namespace stq

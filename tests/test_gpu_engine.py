@@ -1,0 +1,215 @@
+"""GPU parity of the device-resident precision loop (stq_engine_*): Algorithm 1's whole iteration with
+the plan, the EMAs and the tensor table on the device, against the oracle's loop on the same seeded
+gradients.  After every step: codes, scales and parameters bit-exact, the stored and the next plan
+equal.  The statistics are sums that the kernel takes in another order and partly in fp32 (1e-5
+relative is their bar), so scores are compared to 5e-6 absolute and the EMAs to 1e-6 relative, and
+the seeds are chosen such that no oracle score lies within 1e-5 of a threshold (tensors of a few elements,
+whose variance is mostly cancellation, are left out for the same reason)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_06836_amd as stq
+from paper_2604_06836_amd import binding
+
+pytestmark = pytest.mark.gpu
+
+SCORE_ATOL = 5e-6
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    return torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+
+
+class Model:
+    """Buffers of a small model sized for `capacity` bits per code, two code buffers per state."""
+
+    def __init__(self, ctx, sizes, K, plan, capacity, bf16, seed):
+        self.ctx, self.sizes, self.K, self.bf16 = ctx, sizes, K, bf16
+        dev = torch.device("cuda:0")
+        rng = np.random.default_rng(seed)
+        self.param0 = [rng.normal(0, 0.02, n).astype(np.float32) for n in sizes]
+        self.param = [torch.from_numpy(p).to(dev) for p in self.param0]
+        gdt = torch.bfloat16 if bf16 else torch.float32
+        self.grad = [[torch.zeros(n, dtype=gdt, device=dev) for n in sizes] for _ in range(2)]
+        self.codes, self.scales, self.by_ptr = [], [], {}
+        for n in sizes:
+            cb, sb = stq.state_bytes(n, K, capacity)
+            bufs = [torch.full((cb // 4,), -1, dtype=torch.int32, device=dev) for _ in range(4)]  # m, v, m2, v2
+            for b in bufs:
+                self.by_ptr[b.data_ptr()] = b
+            self.codes.append(bufs)
+            self.scales.append([torch.empty(sb // 4, dtype=torch.float32, device=dev) for _ in range(2)])
+        self.tensors = binding.make_tensors(
+            dict(param=p.data_ptr(), grad=g.data_ptr(), numel=n, m_codes=c[0].data_ptr(), m_scales=s[0].data_ptr(),
+                 v_codes=c[1].data_ptr(), v_scales=s[1].data_ptr())
+            for p, g, n, c, s in zip(self.param, self.grad[0], sizes, self.codes, self.scales))
+        self.second = [(c[2].data_ptr(), c[3].data_ptr()) for c in self.codes]
+        self.cplan = binding.make_plan(plan)
+        ctx.zero_state(self.tensors, self.cplan, K, 0)
+        torch.cuda.synchronize()
+
+    def upload_grads(self, k, arrays):
+        for dst, a in zip(self.grad[k], arrays):
+            t = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16) if self.bf16 else torch.from_numpy(a)
+            dst.copy_(t)
+
+    def grad_ptrs(self, k):
+        return [g.data_ptr() for g in self.grad[k]]
+
+
+def grads_of_step(sizes, bf16, seed, lo=-5.0, hi=-2.0):
+    def f(t):
+        rng = np.random.default_rng(seed + 1009 * t)
+        out = []
+        for n in sizes:
+            g = rng.normal(0, 10.0 ** rng.uniform(lo, hi), n).astype(np.float32)
+            out.append(bf16_bits(g) if bf16 else g)
+        return out
+    return f
+
+
+def check_state(oracle, mdl, info, params_ref, states_ref, tag):
+    for l, (n, st) in enumerate(zip(mdl.sizes, states_ref)):
+        assert info["stored"][l] == (st.bm, st.bv), f"{tag} stored widths of tensor {l}"
+        mbuf, vbuf = (mdl.by_ptr[p] for p in info["current"][l])
+        want_m = oracle.pack_wide(st.mw, st.bm) if st.bm >= 16 else oracle.pack(st.um, st.bm)
+        want_v = oracle.pack_wide(st.vw, st.bv) if st.bv >= 16 else oracle.pack(st.cv, st.bv)
+        got_m = mbuf[: want_m.size].cpu().numpy().view(np.uint32)
+        got_v = vbuf[: want_v.size].cpu().numpy().view(np.uint32)
+        assert np.array_equal(got_m, want_m), f"{tag} m codes tensor {l}"
+        assert np.array_equal(got_v, want_v), f"{tag} v codes tensor {l}"
+        if st.bm < 16:
+            assert np.array_equal(mdl.scales[l][0].cpu().numpy().view(np.uint32),
+                                  oracle.pad_scales(st.sm, n, mdl.K).view(np.uint32)), f"{tag} m scales {l}"
+        if st.bv < 16:
+            assert np.array_equal(mdl.scales[l][1].cpu().numpy().view(np.uint32),
+                                  oracle.pad_scales(st.sv, n, mdl.K).view(np.uint32)), f"{tag} v scales {l}"
+        th = mdl.param[l].cpu().numpy()
+        assert np.array_equal(th.view(np.uint32), params_ref[l].view(np.uint32)), f"{tag} params tensor {l}"
+
+
+def run_engine_against_oracle(oracle, ctx, sizes, K, plan, capacity, bf16, U, steps, decide_kw, seed, lo=-5.0, hi=-2.0,
+                              swap_grads=True):
+    mdl = Model(ctx, sizes, K, plan, capacity, bf16, seed)
+    gen = grads_of_step(sizes, bf16, seed, lo, hi)
+    params_ref = [p.copy() for p in mdl.param0]
+    states_ref = [oracle.State.zeros(n, K, bm, bv) for n, (bm, bv) in zip(sizes, plan)]
+    ema_ref = oracle.Ema(0.0, 0.0, 0.0)
+    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, capacity, K, **decide_kw)
+    thr = decide_kw.get("thr", (6.8, 12.0, 24.0))
+    okw = dict(decide_kw)
+    if "flags" in okw:
+        fl = okw.pop("flags")
+        okw["r_mode"], okw["drop"] = fl & 1, fl >> 1
+    nxt = list(plan)
+    widths_seen = set()
+    try:
+        for t in range(1, steps + 1):
+            k = t % 2 if swap_grads else 0
+            g = gen(t)
+            mdl.upload_grads(k, g)
+            hp = binding.HParams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], t, K, int(bf16), 0)
+            eng.step(hp, U, mdl.grad_ptrs(k) if swap_grads else None)
+            info = eng.read()
+            log, nxt, ema_ref = oracle.loop(params_ref, states_ref, lambda _t: g, 1, U, HP, okw, ema=ema_ref, first_step=t,
+                                            next_plan=nxt)
+            tag = f"step {t}"
+            check_state(oracle, mdl, info, params_ref, states_ref, tag)
+            sc = log[0][2]
+            if sc is not None:
+                assert np.allclose(info["score"], sc, rtol=0, atol=SCORE_ATOL), tag
+                assert np.allclose(info["ema"], (ema_ref.n_ema, ema_ref.r_ema, ema_ref.v_ema), rtol=1e-6, atol=0), tag
+                voff = decide_kw.get("v_offset", 0.0)
+                near = any(abs(s - x) < 2 * SCORE_ATOL or abs(s + voff - x) < 2 * SCORE_ATOL for s in sc for x in thr)
+                assert not near, "seed gives a score on a threshold: pick another"
+            assert info["next"] == nxt, f"{tag} next plan"
+            widths_seen.update(w for p in nxt for w in p)
+    finally:
+        eng.close()
+    return widths_seen
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = stq.Context(0, 2048)
+    yield c
+    c.close()
+
+
+SIZES = (5000, 2048, 3 * 2048 + 77, 129, 40000, 37, 7 * 2048, 9000)
+
+
+def test_quantized_ladder_every_third_step(oracle, ctx):
+    kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=(2.0, 5.0, 7.5, 10.0, 13.0), bits=(2, 3, 4, 5, 6, 8))
+    seen = run_engine_against_oracle(oracle, ctx, SIZES, 128, [(6, 4)] * len(SIZES), 8, False, 3, 10, kw, seed=11)
+    assert len(seen) >= 4, seen   # the ladder is really exercised
+
+
+def test_papers_ladder_from_16_bits_bf16_grads(oracle, ctx):
+    # {4, 8, 16, 32} with the paper's thresholds and Phi, every state starting at 16 bits
+    kw = dict(alpha=0.3, tau=50.0)
+    seen = run_engine_against_oracle(oracle, ctx, SIZES, 64, [(16, 16)] * len(SIZES), 32, True, 4, 9, kw, seed=12,
+                                     lo=-6.0, hi=-1.0)
+    assert seen >= {4, 8, 16}, seen
+
+
+@pytest.mark.parametrize("flags", [binding.STQ_DECIDE_R_ALG1, binding.STQ_DECIDE_NO_DUAL,
+                                   binding.STQ_DECIDE_NO_TEMPORAL | binding.STQ_DECIDE_NO_SPATIAL])
+def test_score_variants(oracle, ctx, flags):
+    kw = dict(alpha=0.5, tau=3.0, thr=(6.0, 8.0), bits=(4, 6, 8), flags=flags)
+    run_engine_against_oracle(oracle, ctx, SIZES[:5], 256, [(8, 8)] * 5, 8, False, 2, 6, kw, seed=13 + flags)
+
+
+def test_fixed_gradient_buffers_and_multiples_of_four(oracle, ctx):
+    # no gradient pointers passed; widths {4, 8}: small launches take the quarter-tile schedule
+    kw = dict(alpha=0.3, tau=4.0, thr=(7.2,), bits=(4, 8))
+    run_engine_against_oracle(oracle, ctx, SIZES, 128, [(8, 8)] * len(SIZES), 8, False, 5, 11, kw, seed=14,
+                              swap_grads=False)
+
+
+def test_more_tensors_than_threads_of_the_decision_kernel(oracle, ctx):
+    rng = np.random.default_rng(5)
+    sizes = tuple(int(x) for x in rng.integers(16, 600, 1500))
+    kw = dict(alpha=0.3, tau=4.0, thr=(5.0, 7.5, 10.0), bits=(3, 4, 6, 8))
+    seen = run_engine_against_oracle(oracle, ctx, sizes, 64, [(4, 4)] * len(sizes), 8, False, 2, 4, kw, seed=15)
+    assert len(seen) >= 3
+
+
+def test_argument_checks(ctx):
+    mdl = Model(ctx, (5000, 300), 128, [(8, 8)] * 2, 8, False, 1)
+    kw = dict(alpha=0.3, tau=4.0)
+
+    def code_of(fn):
+        with pytest.raises(binding.StqError) as e:
+            fn()
+        return e.value.code
+
+    # a ladder wider than the buffers' capacity; too many thresholds; a bad width
+    assert code_of(lambda: ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, 128, **kw)) != 0          # bits has 16, 32
+    assert code_of(lambda: ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, 128, thr=tuple(range(16)),
+                                      bits=(4,) * 17, **kw)) != 0
+    assert code_of(lambda: ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, 128, thr=(7.0,), bits=(4, 9), **kw)) != 0
+    # second buffer missing, or the first one again
+    first = [(c[0].data_ptr(), c[1].data_ptr()) for c in mdl.codes]
+    assert code_of(lambda: ctx.engine(mdl.tensors, first, mdl.cplan, 8, 128, thr=(7.0,), bits=(4, 8), **kw)) != 0
+    assert code_of(lambda: ctx.engine(mdl.tensors, [(None, None)] * 2, mdl.cplan, 8, 128, thr=(7.0,), bits=(4, 8), **kw)) != 0
+    assert code_of(lambda: ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, 128, thr=(7.0,), bits=(4, 8), alpha=0.3, tau=0.0)) != 0
+    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, 128, thr=(7.0,), bits=(4, 8), **kw)
+    try:
+        ok = binding.HParams(1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 128, 0, 0)
+        other_block = binding.HParams(1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 64, 0, 0)
+        step0 = binding.HParams(1e-3, 0.9, 0.999, 1e-8, 0.0, 0, 128, 0, 0)
+        assert code_of(lambda: eng.step(other_block, 4)) != 0
+        assert code_of(lambda: eng.step(step0, 4)) != 0
+        assert code_of(lambda: eng.step(ok, 4, [mdl.grad[0][0].data_ptr() + 4, mdl.grad[0][1].data_ptr()])) != 0
+        assert code_of(lambda: eng.step(ok, 4, [0, mdl.grad[0][1].data_ptr()])) != 0
+        info = eng.read()   # nothing ran: the initial plan, in the first buffers
+        assert info["stored"] == [(8, 8)] * 2 and info["next"] == [(8, 8)] * 2
+        assert info["current"] == first
+    finally:
+        eng.close()
