@@ -6,20 +6,22 @@
  * [logarithmic] per Section 3.5, bias correction of the quantized moments,
  * decoupled-weight-decay update), the per-layer statistics the Score Engine of
  * Section 3.3 consumes, the conversion of stored codes when Map (Section 3.4)
- * changes a layer's bit-width, and the host-side decision itself.
+ * changes a layer's bit-width, the host-side decision itself, and the same loop
+ * with the decision and the bit plan resident on the device (stq_engine_*).
  *
  * Conventions
  *   - Every function returns STQ_OK (0) or a negative STQ_E* code.  Nothing
  *     throws, aborts or prints.  stq_strerror() names a code.
  *   - "device" pointers are HIP device memory on the context's GPU, owned by the
- *     caller; the library never allocates or frees per call.  "host" pointers
- *     are ordinary process memory.
+ *     caller; only stq_init and stq_engine_create allocate, only stq_destroy and
+ *     stq_engine_destroy free.  "host" pointers are ordinary process memory.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     stq_zero_state, stq_step, stq_step_transition, stq_repack and stq_repack_many
  *     are asynchronous on that stream; stq_stats synchronises it.  stq_step,
  *     stq_step_transition and stq_repack_many upload a small table from pinned host
  *     memory (and may wait for an upload four calls earlier to have finished), so
- *     they cannot be recorded into a HIP graph.
+ *     they cannot be recorded into a HIP graph.  stq_engine_step is asynchronous too;
+ *     with grads = NULL it consists of kernel launches only.
  *   - One context serves one stream at a time.  Calls on one context must not
  *     overlap from several host threads.
  *
