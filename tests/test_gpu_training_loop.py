@@ -4,6 +4,7 @@ update cadence, compared with torch's fp32 AdamW on the same data and initial we
 
 Two ladders: the paper's own {4, 8, 16, 32} starting from its initial width 16, and the same clamped
 to the block-quantized widths (16 and 32 -> 8).  The statistics of step t come out of step t's kernel, so a new plan takes effect at step t+1.
+A second test runs the same loop through the device-resident engine (stq_engine_*).
 No oracle here: this checks that the pieces work together as an optimizer (loss parity), the
 element-wise parity of every piece is in the other GPU tests.
 """
@@ -107,6 +108,55 @@ def train_quantized(steps, fixed_plan=None, ladder=(4, 8, 8, 8), start=(8, 8)):
     torch.cuda.synchronize()
     ctx.close()
     return losses, widths
+
+
+def train_engine(steps, ladder=(4, 8, 16, 32), start=(16, 16)):
+    """The same loop through stq_engine_*: the host enqueues one call per step and never reads anything back."""
+    m = make_model(0)
+    params = [p for p in m.parameters()]
+    L = len(params)
+    ctx = stq.Context(0, L)
+    stream = torch.cuda.current_stream().cuda_stream
+    cap = max(max(ladder), *start)
+    keep = []
+    for p in params:
+        cm, sb = stq.state_bytes(p.numel(), K, cap)
+        keep.append(([torch.empty(cm // 4, dtype=torch.int32, device="cuda") for _ in range(4)],
+                     [torch.empty(sb // 4, dtype=torch.float32, device="cuda") for _ in range(2)]))
+    loss = torch.nn.functional.mse_loss(m(torch.zeros(1, 32, device="cuda")), torch.zeros(1, 1, device="cuda"))
+    loss.backward()   # gradient buffers to create the engine with; each step passes its own
+    tensors = binding.make_tensors(dict(param=p.data_ptr(), grad=p.grad.data_ptr(), numel=p.numel(),
+                                        m_codes=c[0].data_ptr(), m_scales=s[0].data_ptr(),
+                                        v_codes=c[1].data_ptr(), v_scales=s[1].data_ptr())
+                                   for p, (c, s) in zip(params, keep))
+    plan = binding.make_plan([start] * L)
+    ctx.zero_state(tensors, plan, K, stream)
+    eng = ctx.engine(tensors, [(c[2].data_ptr(), c[3].data_ptr()) for c, _ in keep], plan, cap, K,
+                     alpha=0.1, tau=100.0, thr=(6.8, 12.0, 24.0), bits=ladder, stream=stream)
+    losses = []
+    for t, (x, y) in enumerate(batches(steps, 1), start=1):
+        for p in params:
+            p.grad = None
+        loss = torch.nn.functional.mse_loss(m(x), y)
+        loss.backward()
+        losses.append(loss.detach())
+        eng.step(binding.HParams(LR, BETAS[0], BETAS[1], EPS, WD, t, K, 0, 0), U, [p.grad.data_ptr() for p in params], stream)
+    final = eng.read(stream)["stored"]
+    eng.close()
+    ctx.close()
+    return [float(x) for x in losses], final
+
+
+def test_device_resident_loop_trains_like_fp32_adamw():
+    steps = 400
+    ref = train_fp32(steps)
+    host, _ = train_quantized(steps, ladder=(4, 8, 16, 32), start=(16, 16))
+    dev, final = train_engine(steps)
+    tail = lambda xs: float(np.mean(xs[-50:]))
+    assert tail(dev) <= 1.25 * tail(ref) + 1e-3, (tail(dev), tail(ref))
+    assert abs(tail(dev) - tail(host)) <= 0.05 * tail(host), (tail(dev), tail(host))   # same decisions, same path
+    assert any(w != 16 for p in final for w in p) and all(w in (4, 8, 16, 32) for p in final for w in p)
+    print("final losses: fp32 %.4f, host loop %.4f, device loop %.4f; final plan %s" % (tail(ref), tail(host), tail(dev), final))
 
 
 def test_quantized_adam_trains_like_fp32_adamw():
