@@ -87,9 +87,12 @@ typedef struct {
   uint32_t step;       /* t >= 1, used for the bias corrections 1 - beta^t                */
   uint32_t block;      /* block size K: 64, 128 or 256                                    */
   uint32_t grad_dtype; /* 0 = fp32, 1 = bf16                                              */
-  uint32_t flags;      /* bit 0: accumulate the per-layer statistics during this step     */
+  uint32_t flags;      /* STQ_FLAG_* below                                                */
 } stq_hparams;
-#define STQ_FLAG_STATS 1u
+#define STQ_FLAG_STATS 1u      /* accumulate every per-layer statistic of stq_layer_stats during this step */
+#define STQ_FLAG_STATS_GRAD 2u /* accumulate only the gradient's (count, g_sum, g_abs_sum, g_sq_sum, g_absmax:
+                                  all that stq_decide reads); the moments' fields stay 0.  Cheaper: the kernel
+                                  keeps the plain step's occupancy.  STQ_FLAG_STATS wins if both are set. */
 
 /* Host copy of one layer's accumulated statistics (Section 3.3 inputs plus the
  * moments' own statistics and quantization error).  m and v are the new moments

@@ -14,6 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("STQ_LIBRARY", os.path.join(_PKG, "libstq.so"))  # override: another build of the same ABI
 
 STQ_FLAG_STATS = 1
+STQ_FLAG_STATS_GRAD = 2
 STQ_DECIDE_R_ALG1 = 1
 STQ_DECIDE_NO_DUAL, STQ_DECIDE_NO_TEMPORAL, STQ_DECIDE_NO_SPATIAL = 2, 4, 8
 

@@ -237,9 +237,12 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   a.decay = 1.0f - hp->lr * hp->weight_decay;
   a.lgK = static_cast<uint32_t>(lg_block(hp->block));
 
-  const bool want_stats = (hp->flags & STQ_FLAG_STATS) != 0;
-  // the plain kernel fits six waves per SIMD (three workgroups per CU), the statistics variant two
-  const uint32_t cap_cu = (want_stats || mode == 2) ? 2 : 8;
+  // statistics: all of them, or only the gradient's (the flag for all wins)
+  const int stats = (hp->flags & STQ_FLAG_STATS) ? 1 : ((hp->flags & STQ_FLAG_STATS_GRAD) ? 2 : 0);
+  const bool want_stats = stats != 0;
+  // the plain kernel and the gradient-statistics one fit six waves per SIMD (three workgroups per CU),
+  // the full statistics variant and the wide-state one two workgroups
+  const uint32_t cap_cu = (stats == 1 || mode == 2) ? 2 : 8;
   const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
   const uint32_t wpg = kWavesPerGroup;
   const uint32_t max_groups = ctx->n_cu * per_cu;
@@ -250,13 +253,16 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   const uint64_t units = static_cast<uint64_t>(total) << (quarters ? 2 : 0);
   const uint64_t need_groups = (units + wpg - 1) / wpg;
   const uint32_t groups = static_cast<uint32_t>(need_groups < max_groups ? need_groups : max_groups);
-  // order of the units (see step_kernel): one contiguous range per wave when statistics are collected,
-  // else interleaved chunks -- single units, or four at a time once a wave has many of them
+  // order of the units (see step_kernel): one contiguous range per wave when every statistic is collected,
+  // else interleaved chunks -- single units, or four at a time once a wave has many of them (the
+  // gradient-statistics variant: four at a time in a large launch, else one range per wave)
   const uint64_t n_waves = static_cast<uint64_t>(groups) * wpg;
   const uint64_t per_wave = (units + n_waves - 1) / n_waves;
-  a.chunk = static_cast<uint32_t>(want_stats ? per_wave : (per_wave >= 64 ? 4 : 1));
+  if (stats == 1) a.chunk = static_cast<uint32_t>(per_wave);
+  else if (stats == 2) a.chunk = static_cast<uint32_t>(per_wave >= 64 ? 4 : per_wave);  // its flush is cheap
+  else a.chunk = per_wave >= 64 ? 4 : 1;
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
-  return launch_step(a, hp->grad_dtype == 1, want_stats, mode, groups, stream) == 0 ? STQ_OK : STQ_EHIP;
+  return launch_step(a, hp->grad_dtype == 1, stats, mode, groups, stream) == 0 ? STQ_OK : STQ_EHIP;
 }
 
 }  // namespace stq
@@ -326,7 +332,7 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
     quarters_ok = quarters_ok && ((d.bm | d.bv | d.bm_out | d.bv_out) & 3u) == 0;
   }
   if (int e = launch_table(ctx, ctx->d_desc[table], n, total, ctx->d_stats, hp, mode, quarters_ok, stream)) return e;
-  if ((hp->flags & STQ_FLAG_STATS) != 0)
+  if ((hp->flags & (STQ_FLAG_STATS | STQ_FLAG_STATS_GRAD)) != 0)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;
 }

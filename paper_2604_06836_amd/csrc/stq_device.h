@@ -79,7 +79,8 @@ struct RepackManyArgs {
 };
 
 // Launchers implemented in stq_step.hip and stq_kernels.hip.  `stream` is a hipStream_t.  Return a hipError_t as int.
-int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, int mode, uint32_t groups, void* stream);
+// stats: 0 none, 1 every statistic, 2 the gradient's only.
+int launch_step(const StepArgs& a, bool grad_bf16, int stats, int mode, uint32_t groups, void* stream);
 int launch_zero(const ZeroArgs& a, void* stream);
 int launch_repack(const RepackArgs& a, void* stream);
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream);

@@ -264,7 +264,7 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
   }
   const bool due = stq_decide_due(hp->step, update_every) != 0;
   stq_hparams h = *hp;
-  h.flags = due ? STQ_FLAG_STATS : 0u;
+  h.flags = due ? STQ_FLAG_STATS_GRAD : 0u;  // the decision reads the gradient's sums only
   // kernel variant: the widths in the table differ from the stored ones only in the step after a decision
   const int mode = e->wide ? 2 : (e->pending ? 1 : 0);
   if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;

@@ -135,27 +135,53 @@ __device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n
 // the places that add to them: slot k of lane j is acc[k*64 + j].  Slots 0..8 are fp32 sums of the
 // lane since the last widening, 9..11 running maxima (as bit patterns: all are non-negative)
 // since the last flush; lane k < 9 of slot 12/13 holds the fp64 total of sum k for the current tensor.
-enum LaneSlot { kLGSum = 0, kLGAbs, kLGSq, kLMSum, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr, kLGMax, kLMMax, kLVMax, kLWide };
-constexpr int kStatLdsWords = 14 * 64;
+enum LaneSlot { kLGSum = 0, kLGAbs, kLGSq, kLMSum, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr };
+// S = 1: all of the above and the three maxima, in LDS as described.  S = 2: the gradient's three sums
+// and its maximum only (what the bit-width decision consumes): four registers per lane, and the wave's
+// three fp64 totals in LDS -- within the plain kernel's register and LDS budget.
+template <int S>
 struct LaneStats {
+  static constexpr int kSums = S == 1 ? 9 : 3;
+  static constexpr int kMaxes = S == 1 ? 3 : 1;
+  static constexpr int kMaxSlot = kSums;            // + 0 gradient, 1 first moment, 2 second moment
+  static constexpr int kWideSlot = kSums + kMaxes;  // S = 1: two slots, 64 doubles
+  static constexpr int kWords = S == 0 ? 0 : (S == 1 ? (kSums + kMaxes + 2) * 64 : 8);
   float* acc;      // this wave's slice, null in the plain kernel
   uint32_t tiles;  // tiles since the last widening (uniform)
-  __device__ __forceinline__ void add(int slot, int lane, float x) { acc[slot * 64 + lane] += x; }
-  __device__ __forceinline__ void max_bits(int slot, int lane, float x) {
-    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + slot * 64 + lane;
+  float g[3];      // S = 2: the lane's sums since the last widening
+  uint32_t gmax;   // S = 2: bit pattern of the lane's running max |g|
+  __device__ __forceinline__ void add(int slot, int lane, float x) {
+    if (S == 2) g[slot] += x; else acc[slot * 64 + lane] += x;
+  }
+  __device__ __forceinline__ void max_bits(int which, int lane, float x) {
+    if (S == 2) { gmax = max(gmax, f2u(x)); return; }
+    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + (kMaxSlot + which) * 64 + lane;
     *p = max(*p, f2u(x));
   }
-  __device__ __forceinline__ double& wide(int lane) { return reinterpret_cast<double*>(acc + kLWide * 64)[lane]; }
+  __device__ __forceinline__ float sum(int k, int lane) const { return S == 2 ? g[k] : acc[k * 64 + lane]; }
+  __device__ __forceinline__ float lane_max(int which, int lane) const {
+    return S == 2 ? u2f(gmax) : acc[(kMaxSlot + which) * 64 + lane];
+  }
+  // fp64 total of sum `lane` for the current tensor: lanes below kSums only
+  __device__ __forceinline__ double& wide(int lane) {
+    return reinterpret_cast<double*>(S == 2 ? acc : acc + kWideSlot * 64)[lane];
+  }
   __device__ __forceinline__ void clear_sums(int lane) {
 #pragma unroll
-    for (int k = 0; k < 9; ++k) acc[k * 64 + lane] = 0.0f;
+    for (int k = 0; k < kSums; ++k) {
+      if (S == 2) g[k] = 0.0f; else acc[k * 64 + lane] = 0.0f;
+    }
     tiles = 0;
   }
   __device__ __forceinline__ void clear_all(int lane) {
     clear_sums(lane);
+    if (S == 2) {
+      gmax = 0u;
+    } else {
 #pragma unroll
-    for (int k = 9; k < 12; ++k) acc[k * 64 + lane] = 0.0f;
-    wide(lane) = 0.0;
+      for (int k = 0; k < kMaxes; ++k) acc[(kMaxSlot + k) * 64 + lane] = 0.0f;
+    }
+    if (lane < kSums) wide(lane) = 0.0;
   }
 };
 
@@ -171,26 +197,28 @@ __device__ __forceinline__ float wave_max(float x) {
 }
 
 // fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
-__device__ __forceinline__ void widen_stats(LaneStats& s, int lane) {
+template <int S>
+__device__ __forceinline__ void widen_stats(LaneStats<S>& s, int lane) {
 #pragma unroll
-  for (int k = 0; k < 9; ++k) {
-    const double t = wave_sum(static_cast<double>(s.acc[k * 64 + lane]));
+  for (int k = 0; k < LaneStats<S>::kSums; ++k) {
+    const double t = wave_sum(static_cast<double>(s.sum(k, lane)));
     if (lane == k) s.wide(lane) += t;
   }
   s.clear_sums(lane);
 }
 
-__device__ __forceinline__ void flush_stats(LaneStats& s, double* slot, int lane) {
+template <int S>
+__device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int lane) {
   widen_stats(s, lane);
-  const float gm = wave_max(s.acc[kLGMax * 64 + lane]), mm = wave_max(s.acc[kLMMax * 64 + lane]),
-              vm = wave_max(s.acc[kLVMax * 64 + lane]);
-  if (lane < 9) atomicAdd(&slot[lane], s.wide(lane));
+  float mx[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int k = 0; k < LaneStats<S>::kMaxes; ++k) mx[k] = wave_max(s.lane_max(k, lane));
+  if (lane < LaneStats<S>::kSums) atomicAdd(&slot[lane], s.wide(lane));
   if (lane == 0) {
     // non-negative floats order like their bit patterns
-    uint32_t* mx = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);
-    atomicMax(&mx[0], f2u(gm));
-    atomicMax(&mx[1], f2u(mm));
-    atomicMax(&mx[2], f2u(vm));
+    uint32_t* out = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);
+#pragma unroll
+    for (int k = 0; k < LaneStats<S>::kMaxes; ++k) atomicMax(&out[k], f2u(mx[k]));
   }
   s.clear_all(lane);
 }
@@ -279,12 +307,12 @@ __device__ __forceinline__ float updated_param(float theta, float mt, float den,
 // vq, which takes only 2^b values per block: with TABLE they (and their reciprocals) are read from
 // the per-wave table DEN, indexed by (row, block, code); otherwise they are computed per element.
 // mq holds the quantized first moments; theta is replaced by the new parameters.
-template <bool STATS, bool TAIL, bool TABLE, bool FAST>
+template <int STATS, bool TAIL, bool TABLE, bool FAST>
 __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (&mq)[8], float (&theta)[8],
                                               uint32_t (&code)[8], const float (&sn)[2], const float (&inv)[2],
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
                                               const uint32_t (&den_row)[2], const UpdateArgs& u, uint32_t q, int lane,
-                                              uint32_t n_valid, LaneStats& st) {
+                                              uint32_t n_valid, LaneStats<STATS>& st) {
   float sv_sum = 0.0f, sv_sq = 0.0f, sv_err = 0.0f;  // this quarter's part of the lane sums
 #pragma unroll
   for (int n = 0; n < 8; ++n) {
@@ -296,7 +324,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
     uint32_t c = e.y + (bits >= e.x ? 1u : 0u);
     if (TAIL && !is_valid(n, q, lane, n_valid)) c = 0;
     code[n] = c;
-    if (STATS) {
+    if (STATS == 1) {
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
       const float d = v[n] - vq;
@@ -322,7 +350,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
       }
     }
   }
-  if (STATS) {
+  if (STATS == 1) {
     st.add(kLVSum, lane, sv_sum);
     st.add(kLVSq, lane, sv_sq);
     st.add(kLVErr, lane, sv_err);
@@ -343,10 +371,10 @@ __device__ __forceinline__ float bf16_rne(float x) {
 // MODE 0: widths stay as they are; 1: the launch changes widths (other destination buffers);
 // 2: as 1, and states may have the wide formats: 32 bits = the fp32 value, 16 bits = its bfloat16
 // rounding, stored in the same tile format with 32- or 16-bit codes and without scales.
-template <bool BF16, bool STATS, bool TAIL, int MODE>
+template <bool BF16, int STATS, bool TAIL, int MODE>
 __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t tile, uint32_t q, uint32_t n_valid,
                                                 const StepArgs& a, const uint32_t* lds, uint32_t* ws, int lane,
-                                                uint32_t& carry_m, uint32_t& carry_v, LaneStats& st) {
+                                                uint32_t& carry_m, uint32_t& carry_v, LaneStats<STATS>& st) {
   // Everything derived from the lane index and the block size is cheap to recompute.  Hide the two
   // from loop-invariant code motion, which would otherwise keep dozens of such values live across
   // the whole tile loop and spill them.
@@ -440,7 +468,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     st.add(kLGSum, lane, sg_sum);
     st.add(kLGAbs, lane, sg_abs);
     st.add(kLGSq, lane, sg_sq);
-    st.max_bits(kLGMax, lane, sg_max);
+    st.max_bits(0, lane, sg_max);
   }
 
   // ---- moments: m_t = beta1*m_{t-1} + (1-beta1)*g ; v_t = beta2*v_{t-1} + (1-beta2)*g^2 ----
@@ -523,8 +551,8 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     if (lgK == 8) rb = max(rb, dpp_u32<kDppMirror>(rb));
     r = u2f(rb);
   }
-  if (STATS) {
-    st.max_bits(vL < 2 ? kLMMax : kLVMax, lane, r);
+  if (STATS == 1) {
+    st.max_bits(vL < 2 ? 1 : 2, lane, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
@@ -592,7 +620,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const float mq = bmo == 32 ? m[n] : bf16_rne(m[n]);  // pads are 0 and stay 0
-      if (STATS) {
+      if (STATS == 1) {
         const float dd = m[n] - mq;
         sm_sum += m[n];
         sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
@@ -601,7 +629,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       m[n] = mq;
       kept[n] = f2u(mq);
     }
-    if (STATS) {
+    if (STATS == 1) {
       st.add(kLMSum, lane, sm_sum);
       st.add(kLMSq, lane, sm_sq);
       st.add(kLMErr, lane, sm_err);
@@ -637,7 +665,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (TAIL && !is_valid(n, q, lane, n_valid)) u = 0;
       code[n] = u;
       float mq = sn[i] * lds_at(Rreg, (u << 2) | r_base);
-      if (STATS) {
+      if (STATS == 1) {
         if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
         const float dd = m[n] - mq;
         sm_sum += m[n];
@@ -646,7 +674,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       }
       m[n] = mq;
     }
-    if (STATS) {
+    if (STATS == 1) {
       st.add(kLMSum, lane, sm_sum);
       st.add(kLMSq, lane, sm_sq);
       st.add(kLMErr, lane, sm_err);
@@ -661,7 +689,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const float vq = bvo == 32 ? v[n] : bf16_rne(v[n]);
-      if (STATS) {
+      if (STATS == 1) {
         const float dd = v[n] - vq;
         sv_sum += v[n];
         sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
@@ -673,7 +701,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       const float den = __builtin_sqrtf(vt) + ua.eps;
       theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, ua);
     }
-    if (STATS) {
+    if (STATS == 1) {
       st.add(kLVSum, lane, sv_sum);
       st.add(kLVSq, lane, sv_sq);
       st.add(kLVErr, lane, sv_err);
@@ -751,12 +779,12 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // neighbouring addresses, which the memory system serves best.  The statistics variant flushes
 // its sums once per tensor a wave has touched, so the host gives it one chunk per wave (a
 // contiguous range: few tensors per wave).
-// The statistics variant needs about 80 more registers and runs one workgroup per CU at a time
-// (a second workgroup of six waves per CU measured slower).
-template <bool BF16, bool STATS, int MODE>
-__global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
+// STATS 1 (all statistics) needs about 30 more registers and 76 KB of LDS: two workgroups per CU.
+// STATS 2 (the gradient's statistics only) stays within the plain kernel's registers and LDS budget.
+template <bool BF16, int STATS, int MODE>
+__global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
-  __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + (STATS ? kWavesPerGroup * kStatLdsWords : 0)];
+  __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + kWavesPerGroup * LaneStats<STATS>::kWords];
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
   __syncthreads();
 
@@ -783,8 +811,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
   uint32_t l = __builtin_amdgcn_readfirstlane(lo);
   TensorDesc d = load_desc(a.desc, l);
 
-  LaneStats st;
-  st.acc = STATS ? reinterpret_cast<float*>(lds + kLdsWords + wave * kStatLdsWords) : nullptr;
+  LaneStats<STATS> st;
+  st.acc = STATS ? reinterpret_cast<float*>(lds + kLdsWords + wave * LaneStats<STATS>::kWords) : nullptr;
   st.tiles = 0;
   if (STATS) st.clear_all(lane);
   for (; base < total_units; base += n_waves * C) {
@@ -792,10 +820,12 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
     for (uint64_t u = base; u < c_end; ++u) {
       const uint32_t t = static_cast<uint32_t>(u >> qs);
       const uint32_t q_begin = qs ? static_cast<uint32_t>(u & 3u) : 0u, q_end = qs ? q_begin + 1u : 4u;
-      while (t >= d.tile_begin + d.n_tiles) {  // t < total_tiles, so a later tensor holds it
+      if (t >= d.tile_begin + d.n_tiles) {  // t < total_tiles, so a later tensor holds it
         if (STATS) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
-        ++l;
-        d = load_desc(a.desc, l);
+        do {
+          ++l;
+          d = load_desc(a.desc, l);
+        } while (t >= d.tile_begin + d.n_tiles);
       }
       const uint32_t tile = t - d.tile_begin;
       const uint64_t left = d.numel - static_cast<uint64_t>(tile) * kTile;
@@ -818,24 +848,27 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS || MODE == 2) ? 4 : 6) 
 
 }  // namespace
 
+template <int MODE, int STATS>
+static void launch_variant(const StepArgs& a, bool grad_bf16, dim3 grid, dim3 block, hipStream_t s) {
+  if (grad_bf16) hipLaunchKernelGGL((step_kernel<true, STATS, MODE>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((step_kernel<false, STATS, MODE>), grid, block, 0, s, a);
+}
+
 template <int MODE>
-static void launch_variant(const StepArgs& a, bool grad_bf16, bool want_stats, dim3 grid, dim3 block, hipStream_t s) {
-  if (grad_bf16) {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<true, true, MODE>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<true, false, MODE>), grid, block, 0, s, a);
-  } else {
-    if (want_stats) hipLaunchKernelGGL((step_kernel<false, true, MODE>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<false, false, MODE>), grid, block, 0, s, a);
-  }
+static void launch_mode(const StepArgs& a, bool grad_bf16, int stats, dim3 grid, dim3 block, hipStream_t s) {
+  if (stats == 1) launch_variant<MODE, 1>(a, grad_bf16, grid, block, s);
+  else if (stats == 2) launch_variant<MODE, 2>(a, grad_bf16, grid, block, s);
+  else launch_variant<MODE, 0>(a, grad_bf16, grid, block, s);
 }
 
 // mode: 0 in place at unchanged widths, 1 widths change, 2 as 1 with 16- or 32-bit states
-int launch_step(const StepArgs& a, bool grad_bf16, bool want_stats, int mode, uint32_t groups, void* stream) {
+// stats: 0 none, 1 every statistic, 2 the gradient's only
+int launch_step(const StepArgs& a, bool grad_bf16, int stats, int mode, uint32_t groups, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(groups), block(64 * kWavesPerGroup);
-  if (mode == 2) launch_variant<2>(a, grad_bf16, want_stats, grid, block, s);
-  else if (mode == 1) launch_variant<1>(a, grad_bf16, want_stats, grid, block, s);
-  else launch_variant<0>(a, grad_bf16, want_stats, grid, block, s);
+  if (mode == 2) launch_mode<2>(a, grad_bf16, stats, grid, block, s);
+  else if (mode == 1) launch_mode<1>(a, grad_bf16, stats, grid, block, s);
+  else launch_mode<0>(a, grad_bf16, stats, grid, block, s);
   return static_cast<int>(hipGetLastError());
 }
 

@@ -530,3 +530,37 @@ def test_argument_checks(ctx):
     out = (binding.LayerStats * 1)()
     assert lib.stq_stats(ctx._h, out, 1, None) == -7  # nothing accumulated
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------- the gradient-only statistics flag
+@pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64)])
+def test_gradient_only_statistics(oracle, ctx, dtype, K):
+    # STQ_FLAG_STATS_GRAD: the step itself is unchanged, the gradient's sums and maximum agree with the
+    # oracle's, the moments' fields stay zero; also across a width-changing step and with ragged tails
+    sizes = [3 * 2048 + 5, 2048, 100, 20 * 2048 + 777, 64]
+    w = configs.Workload(95, f"gstats-{dtype}", [(f"t{i}", n) for i, n in enumerate(sizes)], K, dtype, 3,
+                         "normal_per_tensor")
+    plan = [(8, 4), (5, 5), (3, 7), (4, 4), (6, 2)]
+    new_plan = [(4, 8), (5, 5), (8, 3), (4, 6), (6, 2)]
+    dm = DeviceModel(ctx, w, plan)
+    th_ref = [p.cpu().numpy().copy() for p in dm.param]
+    st_ref = oracle_states(oracle, w, plan)
+    for t in (1, 2, 3):
+        dm.set_grads(t)
+        if t == 2:
+            dm.step_transition(t, new_plan, stats="grad")
+        else:
+            dm.step(t, stats="grad")
+        torch.cuda.synchronize()
+        got = dm.ctx.stats(len(sizes), dm.stream)
+        for l in range(len(sizes)):
+            bm, bv = new_plan[l] if t >= 2 else plan[l]
+            s = oracle.step_transition(th_ref[l], dm.host_grad(l), st_ref[l], bm, bv, **w.hparams, t=t, want_stats=True)
+            assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"gstats step {t}")
+            g = got[l]
+            assert g.count == s.count
+            for name, scale in (("g_sum", s.g_abs_sum), ("g_abs_sum", s.g_abs_sum), ("g_sq_sum", s.g_sq_sum)):
+                assert abs(getattr(g, name) - getattr(s, name)) <= 1e-5 * scale + s.count * 1.2e-38, (t, l, name)
+            assert g.g_absmax == s.g_absmax
+            for name in ("m_sum", "m_sq_sum", "m_err_sq", "m_absmax", "v_sum", "v_sq_sum", "v_err_sq", "v_absmax"):
+                assert getattr(g, name) == 0, (t, l, name)

@@ -14,10 +14,12 @@ from paper_2604_06836_amd import binding
 from .configs import Workload
 
 
-def hparams(w: Workload, t: int, stats: bool = False) -> binding.HParams:
+def hparams(w: Workload, t: int, stats=False) -> binding.HParams:
+    """stats: False, True (every statistic) or "grad" (the gradient's only)."""
     h = w.hparams
+    flags = stq.STQ_FLAG_STATS_GRAD if stats == "grad" else (stq.STQ_FLAG_STATS if stats else 0)
     return binding.HParams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], t, w.K,
-                           1 if w.grad_dtype == "bf16" else 0, stq.STQ_FLAG_STATS if stats else 0)
+                           1 if w.grad_dtype == "bf16" else 0, flags)
 
 
 class DeviceModel:
@@ -75,7 +77,7 @@ class DeviceModel:
         for l in range(len(self.param)):
             self.grad[l].copy_(self.w.gen_grad(l, step, self.device))
 
-    def step(self, t: int, stats: bool = False):
+    def step(self, t: int, stats=False):
         self.ctx.step(self.tensors, self.cplan, hparams(self.w, t, stats), self.stream)
 
     def _code_words(self, n: int, b: int) -> int:
@@ -131,7 +133,7 @@ class DeviceModel:
         self._adopt(changes, new_plan, binding.make_plan(new_plan), also_patch)
         return len(changes)
 
-    def step_transition(self, t: int, new_plan: Sequence[Tuple[int, int]], stats: bool = False, also_patch=()) -> int:
+    def step_transition(self, t: int, new_plan: Sequence[Tuple[int, int]], stats=False, also_patch=()) -> int:
         """One step that reads the states at the current plan and writes them at new_plan
         (stq_step_transition), then adopts the new buffers and plan.  Returns the number of changed states."""
         changes = self._destinations(new_plan)
