@@ -96,6 +96,10 @@ def main():
                     help="how a new bit plan takes effect: stq_repack_many before the step (the configurations' "
                          "wording), inside the step with stq_step_transition, or (workloads that decide every "
                          "step) the device-resident loop stq_engine_step, which never waits for the GPU")
+    ap.add_argument("--stats", choices=("full", "grad"), default="full",
+                    help="workloads that decide every step: collect every statistic of stq_layer_stats (the "
+                         "configuration's wording) or only the gradient's, which is all the decision reads "
+                         "(the engine always does the latter)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise kernel of known size (scale reference for HBM counters)")
     args = ap.parse_args()
@@ -137,6 +141,7 @@ def main():
         tensor_sets.append(dm.tensors)
 
     decide_every_step = w.transitions == "decide_every_step"
+    stats_arg = ("grad" if args.stats == "grad" else True) if decide_every_step else False
     ema = binding.DecideState(0, 0, 0)
     ladder = None
     kernel_ms, repacked = [], 0
@@ -173,10 +178,10 @@ def main():
                 kernel_ms.append((e0, e1))
             return
         if pending is not None:
-            repacked += dm.step_transition(t, pending, stats=decide_every_step, also_patch=(tensor_sets[1 - k],))
+            repacked += dm.step_transition(t, pending, stats=stats_arg, also_patch=(tensor_sets[1 - k],))
             plan, pending = pending, None
         else:
-            dm.step(t, stats=decide_every_step)
+            dm.step(t, stats=stats_arg)
         e1.record(stream)
         if timed:
             kernel_ms.append((e0, e1))
@@ -231,7 +236,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "configs_index": w.cfg, "params": n, "tensors": L, "block": w.K,
                    "grad_dtype": w.grad_dtype, "avg_state_bits": round(w.avg_bits(plan), 3),
-                   "transition": args.transition, "changed_states_in_timed_region": repacked},
+                   "transition": args.transition, "changed_states_in_timed_region": repacked,
+                   "statistics": ("gradient" if (args.stats == "grad" or args.transition == "engine") else "all")
+                   if decide_every_step else "none"},
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel_ms_avg": k_avg_ms, "algorithmic_bytes_per_param": bpp,
@@ -239,7 +246,7 @@ def main():
     }
     traffic_file = os.path.join(ROOT, "profiles", "step_kernel_traffic.json")
     if os.path.exists(traffic_file):
-        tr = json.load(open(traffic_file)).get(w.name)
+        tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ""))
         if tr:
             out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
     if not args.no_cpu_baseline:

@@ -18,6 +18,7 @@ namespace {
 
 constexpr uint32_t kMaxThr = 15;
 constexpr int kPlanThreads = 1024;
+constexpr uint32_t kPlanLdsLayers = 1024;  // the factors of this many layers are summed from LDS, the rest from global memory
 
 struct PlanCfg {  // the decision's parameters, by value
   double alpha, phi, eps, v_offset;
@@ -53,6 +54,7 @@ __device__ uint32_t map_width(double score, const PlanCfg& c) {
 // the table for the next step.
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanArgs a) {
   __shared__ double sh_ema[3];
+  __shared__ double sh_fac[3][kPlanLdsLayers];
   const uint32_t tid = threadIdx.x;
   for (uint32_t l = tid; l < a.n; l += kPlanThreads) {
     TensorDesc& d = a.desc[l];
@@ -76,14 +78,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanArgs a) {
     if (var < 0.0) var = 0.0;
     const double cv = sqrt(var) / (mean_abs + a.cfg.eps);  // r_l
     a.fac[3 * l] = rms; a.fac[3 * l + 1] = cv; a.fac[3 * l + 2] = mean_sq;
+    if (l < kPlanLdsLayers) { sh_fac[0][l] = rms; sh_fac[1][l] = cv; sh_fac[2][l] = mean_sq; }
     for (int k = 0; k < kStatSlots; ++k) s[k] = 0.0;
   }
   if (!a.decide) return;
   __threadfence_block();
   __syncthreads();
   if (tid < 3) {
-    double sum = 0.0;
-    for (uint32_t l = 0; l < a.n; ++l) sum += a.fac[3 * l + tid];
+    double sum = 0.0;  // in layer order, as the host-side decision sums
+    const uint32_t in_lds = a.n < kPlanLdsLayers ? a.n : kPlanLdsLayers;
+    for (uint32_t l = 0; l < in_lds; ++l) sum += sh_fac[tid][l];
+    for (uint32_t l = in_lds; l < a.n; ++l) sum += a.fac[3 * l + tid];
     const double al = a.cfg.alpha, inv_n = 1.0 / static_cast<double>(a.n);
     const double e = al * (sum * inv_n) + (1.0 - al) * a.ema[tid];  // Eq. 4
     a.ema[tid] = e;

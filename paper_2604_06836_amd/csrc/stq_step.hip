@@ -128,6 +128,16 @@ __device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n
   return (512u * q + static_cast<uint32_t>(256 * (n >> 2) + 4 * lane + (n & 3))) < n_valid;
 }
 
+// x from the lane that a DPP control word names (all lanes of the wave active)
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16 lanes
+
 // -------------------------------------------------------------------- statistics
 // (The sums of squares use fused multiply-adds: the fixed operation order binds the Adam
 // arithmetic, not the statistics, which are compared within a tolerance.)
@@ -137,50 +147,52 @@ __device__ __forceinline__ bool is_valid(int n, uint32_t q, int lane, uint32_t n
 // since the last flush; lane k < 9 of slot 12/13 holds the fp64 total of sum k for the current tensor.
 enum LaneSlot { kLGSum = 0, kLGAbs, kLGSq, kLMSum, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr };
 // S = 1: all of the above and the three maxima, in LDS as described.  S = 2: the gradient's three sums
-// and its maximum only (what the bit-width decision consumes): four registers per lane, and the wave's
-// three fp64 totals in LDS -- within the plain kernel's register and LDS budget.
+// and its maximum only (what the bit-width decision consumes).  Neighbouring lanes 2i, 2i+1 first
+// combine their contributions (one DPP operation) and share word i of a 32-word slot -- both write the
+// same value to it -- which keeps the slice small enough for three workgroups per CU and costs no
+// registers: slots 0..2 sums, slot 3 maximum, then the wave's three fp64 totals.
 template <int S>
 struct LaneStats {
   static constexpr int kSums = S == 1 ? 9 : 3;
   static constexpr int kMaxes = S == 1 ? 3 : 1;
+  static constexpr int kSlotWords = S == 1 ? 64 : 32;
   static constexpr int kMaxSlot = kSums;            // + 0 gradient, 1 first moment, 2 second moment
-  static constexpr int kWideSlot = kSums + kMaxes;  // S = 1: two slots, 64 doubles
-  static constexpr int kWords = S == 0 ? 0 : (S == 1 ? (kSums + kMaxes + 2) * 64 : 8);
+  static constexpr int kWideSlot = kSums + kMaxes;  // S = 1: two slots, 64 doubles; S = 2: 3 doubles
+  static constexpr int kWords = S == 0 ? 0 : (S == 1 ? (kSums + kMaxes + 2) * 64 : (kSums + kMaxes) * 32 + 8);
   float* acc;      // this wave's slice, null in the plain kernel
   uint32_t tiles;  // tiles since the last widening (uniform)
-  float g[3];      // S = 2: the lane's sums since the last widening
-  uint32_t gmax;   // S = 2: bit pattern of the lane's running max |g|
+  __device__ __forceinline__ int word(int slot, int lane) const {
+    return slot * kSlotWords + (S == 2 ? (lane >> 1) : lane);
+  }
   __device__ __forceinline__ void add(int slot, int lane, float x) {
-    if (S == 2) g[slot] += x; else acc[slot * 64 + lane] += x;
+    if (S == 2) x += u2f(dpp_u32<kDppXor1>(f2u(x)));
+    acc[word(slot, lane)] += x;
   }
   __device__ __forceinline__ void max_bits(int which, int lane, float x) {
-    if (S == 2) { gmax = max(gmax, f2u(x)); return; }
-    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + (kMaxSlot + which) * 64 + lane;
-    *p = max(*p, f2u(x));
+    uint32_t xb = f2u(x);
+    if (S == 2) xb = max(xb, dpp_u32<kDppXor1>(xb));
+    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + word(kMaxSlot + which, lane);
+    *p = max(*p, xb);
   }
-  __device__ __forceinline__ float sum(int k, int lane) const { return S == 2 ? g[k] : acc[k * 64 + lane]; }
-  __device__ __forceinline__ float lane_max(int which, int lane) const {
-    return S == 2 ? u2f(gmax) : acc[(kMaxSlot + which) * 64 + lane];
+  // this lane's share of sum k: over the 64 lanes of the wave the shares add up to the wave's sum
+  __device__ __forceinline__ float sum(int k, int lane) const {
+    const float x = acc[word(k, lane)];
+    return (S == 2 && (lane & 1)) ? 0.0f : x;
   }
+  __device__ __forceinline__ float lane_max(int which, int lane) const { return acc[word(kMaxSlot + which, lane)]; }
   // fp64 total of sum `lane` for the current tensor: lanes below kSums only
   __device__ __forceinline__ double& wide(int lane) {
-    return reinterpret_cast<double*>(S == 2 ? acc : acc + kWideSlot * 64)[lane];
+    return reinterpret_cast<double*>(acc + kWideSlot * kSlotWords)[lane];
   }
   __device__ __forceinline__ void clear_sums(int lane) {
 #pragma unroll
-    for (int k = 0; k < kSums; ++k) {
-      if (S == 2) g[k] = 0.0f; else acc[k * 64 + lane] = 0.0f;
-    }
+    for (int k = 0; k < kSums; ++k) acc[word(k, lane)] = 0.0f;
     tiles = 0;
   }
   __device__ __forceinline__ void clear_all(int lane) {
     clear_sums(lane);
-    if (S == 2) {
-      gmax = 0u;
-    } else {
 #pragma unroll
-      for (int k = 0; k < kMaxes; ++k) acc[(kMaxSlot + k) * 64 + lane] = 0.0f;
-    }
+    for (int k = 0; k < kMaxes; ++k) acc[word(kMaxSlot + k, lane)] = 0.0f;
     if (lane < kSums) wide(lane) = 0.0;
   }
 };
@@ -222,16 +234,6 @@ __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int l
   }
   s.clear_all(lane);
 }
-
-// x from the lane that a DPP control word names (all lanes of the wave active)
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
-  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xF, 0xF, true));
-}
-constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
-constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16 lanes
 
 // Correctly rounded square root for x = 0 or 2^-96 <= x <= 2^96: the hardware estimate is within
 // one ulp; the residuals x - next_down*s and x - next_up*s (exact in an fma) tell which of the
@@ -780,7 +782,7 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 // its sums once per tensor a wave has touched, so the host gives it one chunk per wave (a
 // contiguous range: few tensors per wave).
 // STATS 1 (all statistics) needs about 30 more registers and 76 KB of LDS: two workgroups per CU.
-// STATS 2 (the gradient's statistics only) stays within the plain kernel's registers and LDS budget.
+// STATS 2 (the gradient's statistics only) stays within the plain kernel's register and LDS budget.
 template <bool BF16, int STATS, int MODE>
 __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
