@@ -1,6 +1,8 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (all tensors of the workload in one stq_step call).
 
+The last test does the same for the device-resident loop (stq_engine_step).
+
 The oracle cannot run 10^9 elements in seconds, but blocks are independent: for sampled windows of
 whole tiles (and every sampled tensor's ragged last tile) the inputs are copied to the host before
 the step, the oracle is run on the window alone, and codes, scales and parameters of the window are
@@ -142,3 +144,92 @@ def test_tensor_beyond_2_31_elements(oracle):
     ctx.close()
     del dm
     torch.cuda.empty_cache()
+
+
+def _window_of(oracle, w, codes_m, codes_v, dm, l, lo, n, bm, bv):
+    """Host copy of a window's state from explicit code buffers at explicit widths (quantized widths only)."""
+    K, t0, nt = w.K, lo // TILE, (n + TILE - 1) // TILE
+    mw = codes_m[t0 * 64 * bm:(t0 + nt) * 64 * bm].cpu().numpy().view(np.uint32)
+    vw = codes_v[t0 * 64 * bv:(t0 + nt) * 64 * bv].cpu().numpy().view(np.uint32)
+    spt, nb = TILE // K, (n + K - 1) // K
+    ms = dm.m_scales[l][t0 * spt:t0 * spt + nb].cpu().numpy().copy()
+    vs = dm.v_scales[l][t0 * spt:t0 * spt + nb].cpu().numpy().copy()
+    return mw, vw, ms, vs
+
+
+def test_device_resident_loop_at_full_size(oracle):
+    """stq_engine_step on all 388 gpt2-xl tensors, as bench.py --transition engine launches it.  Per step:
+    sampled windows go through the oracle's width-changing step at the widths the engine had decided, and
+    the decision itself is redone by the oracle from float64 reductions of every tensor's gradient."""
+    from paper_2604_06836_amd import binding
+    w = configs.get_workload("gpt2-xl")
+    rng = np.random.default_rng(99)
+    L = len(w.tensors)
+    plan = [(4, 4)] * L
+    ctx = stq.Context(0, L)
+    dm = DeviceModel(ctx, w, plan, spare_width=8)
+    by_ptr = {}
+    for l in range(L):
+        for buf in (dm.m_codes[l], dm.v_codes[l], dm._spare[(l, 0)], dm._spare[(l, 1)]):
+            by_ptr[buf.data_ptr()] = buf
+    second = [(dm._spare[(l, 0)].data_ptr(), dm._spare[(l, 1)].data_ptr()) for l in range(L)]
+    thr, bits = (2.0, 5.0, 7.5, 10.0, 13.0), (2, 3, 4, 5, 6, 8)
+    kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=thr, bits=bits)
+    eng = ctx.engine(dm.tensors, second, dm.cplan, 8, w.K, stream=dm.stream, **kw)
+    ema = oracle.Ema(0.0, 0.0, 0.0)
+    windows = sample_windows(w, rng, n_tensors=8, per_tensor=2)
+    changed = 0
+    try:
+        for t in (1, 2, 3):
+            dm.set_grads(t)
+            info = eng.read(dm.stream)
+            before = []
+            for l, lo, n in windows:
+                bm, bv = info["stored"][l]
+                cm, cv = (by_ptr[p] for p in info["current"][l])
+                mw, vw, ms, vs = _window_of(oracle, w, cm, cv, dm, l, lo, n, bm, bv)
+                th = dm.param[l][lo:lo + n].cpu().numpy().copy()
+                g = dm.grad[l][lo:lo + n].view(torch.int16).cpu().numpy().view(np.uint16).copy()
+                st = oracle.State(n, w.K, bm, bv, um=oracle.unpack(mw, n, bm), sm=ms, cv=oracle.unpack(vw, n, bv), sv=vs)
+                before.append((th, g, st))
+            eng.step(hparams_of(w, t), 1, None, dm.stream)
+            after = eng.read(dm.stream)
+            assert after["stored"] == info["next"], f"step {t}: the step wrote other widths than decided"
+            for (l, lo, n), (th, g, st) in zip(windows, before):
+                bm, bv = info["next"][l]
+                oracle.step_transition(th, g, st, bm, bv, **w.hparams, t=t)
+                cm, cv = (by_ptr[p] for p in after["current"][l])
+                mw, vw, ms, vs = _window_of(oracle, w, cm, cv, dm, l, lo, n, bm, bv)
+                tag = f"engine step {t} tensor {l} window {lo}+{n}"
+                assert np.array_equal(mw, oracle.pack(st.um, bm)), tag + ": m codes"
+                assert np.array_equal(vw, oracle.pack(st.cv, bv)), tag + ": v codes"
+                assert np.array_equal(ms.view(np.uint32), st.sm.view(np.uint32)), tag + ": m scales"
+                assert np.array_equal(vs.view(np.uint32), st.sv.view(np.uint32)), tag + ": v scales"
+                got = dm.param[l][lo:lo + n].cpu().numpy()
+                assert np.array_equal(got.view(np.uint32), th.view(np.uint32)), tag + ": params"
+            # the decision, from float64 reductions of every gradient
+            stats = []
+            for l in range(L):
+                g64 = dm.grad[l].double()
+                s = oracle.Stats()
+                s.count, s.g_sum, s.g_abs_sum, s.g_sq_sum = g64.numel(), float(g64.sum()), float(g64.abs().sum()), float((g64 * g64).sum())
+                stats.append(s)
+            bm_o, bv_o, sc = oracle.decide(ema, stats, t, **kw)
+            assert np.allclose(after["score"], sc, rtol=0, atol=1e-5), f"step {t} scores"
+            assert np.allclose(after["ema"], (ema.n_ema, ema.r_ema, ema.v_ema), rtol=1e-6, atol=0), f"step {t} EMAs"
+            for l in range(L):
+                near = any(abs(sc[l] - x) < 1e-4 or abs(sc[l] - 0.5 - x) < 1e-4 for x in thr)
+                if not near:
+                    assert after["next"][l] == (int(bm_o[l]), int(bv_o[l])), f"step {t} tensor {l}: score {sc[l]}"
+            changed += sum(a != b for a, b in zip(after["next"], after["stored"]))
+        assert changed > L // 4   # widths really moved
+    finally:
+        eng.close()
+        ctx.close()
+    del dm
+    torch.cuda.empty_cache()
+
+
+def hparams_of(w, t):
+    from workloads.harness import hparams
+    return hparams(w, t)
