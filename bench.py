@@ -92,10 +92,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--transition", choices=("repack", "fused", "engine"), default="repack",
+    ap.add_argument("--transition", choices=("repack", "fused", "engine", "engine-alg1"), default="repack",
                     help="how a new bit plan takes effect: stq_repack_many before the step (the configurations' "
                          "wording), inside the step with stq_step_transition, or (workloads that decide every "
-                         "step) the device-resident loop stq_engine_step, which never waits for the GPU")
+                         "step) the device-resident loop stq_engine_step, which never waits for the GPU (engine-alg1: in "
+                         "Algorithm 1's written order, with a pass over the gradients before the step)")
     ap.add_argument("--stats", choices=("full", "grad"), default="full",
                     help="workloads that decide every step: collect every statistic of stq_layer_stats (the "
                          "configuration's wording) or only the gradient's, which is all the decision reads "
@@ -148,9 +149,10 @@ def main():
 
     fused = args.transition == "fused"
     pending = None  # fused mode: the plan that the next step adopts
-    if args.transition == "engine" and not decide_every_step:
+    use_engine = args.transition in ("engine", "engine-alg1")
+    if use_engine and not decide_every_step:
         sys.exit("bench.py: --transition engine is for the workloads that decide every step (gpt2-xl)")
-    if args.transition == "engine" and args.warmup < 1:
+    if use_engine and args.warmup < 1:
         sys.exit("bench.py: --transition engine needs --warmup >= 1 (the first step calibrates the ladder on the host)")
     engine = None   # engine mode: created after the first step has calibrated the ladder
     import ctypes
@@ -196,11 +198,12 @@ def main():
             else:
                 repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
                 plan = new_plan
-            if args.transition == "engine":
+            if use_engine:
                 # hand the loop over to the device: same ladder, the EMAs as they are now
                 second = [(dm._spare[(l, 0)].data_ptr(), dm._spare[(l, 1)].data_ptr()) for l in range(L)]
                 engine = ctx.engine(dm.tensors, second, dm.cplan, 8, w.K, alpha=0.3, tau=4.0, v_offset=-0.5,
-                                    thr=ladder, bits=w.bits_m, ema=ema, stream=dm.stream)
+                                    thr=ladder, bits=w.bits_m, ema=ema, alg1_order=args.transition == "engine-alg1",
+                                    stream=dm.stream)
 
     t = 0
     for _ in range(args.warmup):
@@ -237,7 +240,7 @@ def main():
         "config": {"workload": w.name, "configs_index": w.cfg, "params": n, "tensors": L, "block": w.K,
                    "grad_dtype": w.grad_dtype, "avg_state_bits": round(w.avg_bits(plan), 3),
                    "transition": args.transition, "changed_states_in_timed_region": repacked,
-                   "statistics": ("gradient" if (args.stats == "grad" or args.transition == "engine") else "all")
+                   "statistics": ("gradient" if (args.stats == "grad" or use_engine) else "all")
                    if decide_every_step else "none"},
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
@@ -246,7 +249,7 @@ def main():
     }
     traffic_file = os.path.join(ROOT, "profiles", "step_kernel_traffic.json")
     if os.path.exists(traffic_file):
-        tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ""))
+        tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ("-engine-alg1" if use_engine else "")))
         if tr:
             out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
     if not args.no_cpu_baseline:

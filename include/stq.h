@@ -171,6 +171,14 @@ int stq_step_transition(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
                         const stq_bits* plan_old, const stq_bits* plan_new,
                         const stq_codes* new_codes, const stq_hparams* hp, void* hip_stream);
 
+/* Add the statistics of the gradients alone (count, g_sum, g_abs_sum, g_sq_sum, g_absmax) of the n
+ * tensors to accumulators 0..n-1, without a step: for a caller that follows Algorithm 1's written order
+ * (statistics of g_t -> stq_stats -> stq_decide -> stq_step_transition of the same step t).  One pass
+ * over the gradients; only tensors[l].grad and numel are read (the other fields must still be valid).
+ * Asynchronous; uploads a small table like stq_step. */
+int stq_grad_stats(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, uint32_t block,
+                   uint32_t grad_dtype, void* hip_stream);
+
 /* Copy accumulators 0..n-1 to `out` (host, n entries), synchronise, and clear
  * them on the device.  Sums are order-dependent in the last bits; the maxima
  * are exact. */
@@ -217,11 +225,16 @@ int stq_decide_due(uint32_t step, uint32_t update_every);
  * EMAs -> score -> Map body) with the bit plan, the EMAs and the tensor table living
  * on the device: stq_engine_step only enqueues kernels, nothing is copied back and the
  * host never waits.  The decision is the one stq_decide takes (same formulas, fp64,
- * same order of the sums over the layers; log2 is the device library's); it is made
- * from the gradients of step t inside that step's kernel and takes effect in step
- * t+1, which reads each state at its old width and writes it at the new one (the
- * width-changing step of stq_step_transition). */
+ * same order of the sums over the layers; log2 is the device library's).  Two orders:
+ *   default: the statistics of g_t are a by-product of step t's kernel (no extra pass)
+ *     and the decision takes effect in step t+1, which reads each state at its old
+ *     width and writes it at the new one (the width-changing step of stq_step_transition);
+ *   STQ_ENGINE_ALG1_ORDER: as Algorithm 1 is written -- on a decision step a pass over
+ *     the gradients gathers the statistics, Map sets the widths, and the layer loop of
+ *     the SAME step t writes the states at the new widths (one more read of the
+ *     gradients on decision steps). */
 typedef struct stq_engine stq_engine;
+#define STQ_ENGINE_ALG1_ORDER 1u
 
 /* tensors[l] (host array of n): the parameter, gradient, scale arrays and FIRST code
  * buffers, holding states at the widths of initial_plan (stq_zero_state, or a restored
@@ -230,12 +243,12 @@ typedef struct stq_engine stq_engine;
  * width of initial_plan and of cfg->bits; scale arrays are needed even while a state is
  * 16 or 32 bits wide.  A state lives in one of its two buffers and moves to the other
  * when its width changes.  cfg->n_thr may not exceed 15; cfg is copied.  The EMAs start
- * at *ema (zeros if NULL).  The engine keeps the context's device; destroy it before
- * the context. */
+ * at *ema (zeros if NULL).  flags: 0 or STQ_ENGINE_ALG1_ORDER.  The engine keeps the
+ * context's device; destroy it before the context. */
 int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
                       const stq_codes* second, uint32_t n, const stq_bits* initial_plan,
                       uint32_t capacity_bits, uint32_t block, const stq_decide_cfg* cfg,
-                      const stq_decide_state* ema, void* hip_stream);
+                      const stq_decide_state* ema, uint32_t flags, void* hip_stream);
 
 /* Step hp->step of the loop (hp->block must be the engine's; STQ_FLAG_STATS in hp->flags
  * is ignored: the engine collects statistics exactly when stq_decide_due(hp->step,

@@ -151,6 +151,19 @@ static float bf16_to_f32(uint16_t h) {
   uint32_t w = (uint32_t)h << 16; float f; memcpy(&f, &w, 4); return f;
 }
 
+/* The statistics of one layer's gradient alone (the inputs of Eq. 2, 3 and 8), for the order in which
+ * Algorithm 1 is written: statistics and Map first, then the layer loop of the same step.  The other
+ * fields of *st are left as they are. */
+void stq_oracle_grad_stats(const void* grad, int grad_is_bf16, uint64_t n, stq_oracle_stats* st) {
+  for (uint64_t i = 0; i < n; ++i) {
+    float gf = grad_is_bf16 ? bf16_to_f32(((const uint16_t*)grad)[i]) : ((const float*)grad)[i];
+    double gd = (double)gf;
+    st->g_sum += gd; st->g_abs_sum += fabs(gd); st->g_sq_sum += gd * gd;
+    if (fabsf(gf) > st->g_absmax) st->g_absmax = fabsf(gf);
+  }
+  st->count += n;
+}
+
 /*
  * One Adam step on one tensor ("layer") of `numel` elements with blocks of K
  * consecutive elements (the last block may be shorter).

@@ -106,6 +106,8 @@ def lib():
         L.stq_oracle_unpack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_void_p]
         L.stq_oracle_repack.restype = None
         L.stq_oracle_repack.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        L.stq_oracle_grad_stats.restype = None
+        L.stq_oracle_grad_stats.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.POINTER(Stats)]
         L.stq_oracle_decide.restype = None
         L.stq_oracle_decide_due.restype = C.c_int
         L.stq_oracle_decide_due.argtypes = [C.c_uint32, C.c_uint32]
@@ -328,6 +330,37 @@ def decide(ema: Ema, stats: list, step_t: int, *, alpha=0.1, tau=1000.0, phi=PAP
     sc = np.empty(L, np.float64)
     lib().stq_oracle_decide(C.byref(ema), arr, L, C.byref(cfg), step_t, _p(bm), _p(bv), _p(sc))
     return bm, bv, sc
+
+
+def grad_stats(grad: np.ndarray) -> Stats:
+    """Statistics of a layer's gradient alone (inputs of Eq. 2, 3, 8)."""
+    bf16 = grad.dtype == np.uint16
+    if not bf16:
+        _chk(grad, np.float32)
+    assert grad.flags.c_contiguous
+    st = Stats()
+    lib().stq_oracle_grad_stats(_p(grad), int(bf16), grad.size, C.byref(st))
+    return st
+
+
+def loop_alg1_order(params: list, states: list, grads_of_step, steps: int, U: int, hp: dict, decide_kw: dict,
+                    ema: Ema = None, first_step: int = 1):
+    """Algorithm 1 in the order it is written: at a decision step t the layer statistics of g_t go
+    through the Score Engine and Map FIRST, and the layer loop of the same step t already quantizes at
+    the new widths (reading the stored states at the old ones).  Returns (records (t, plan written in
+    that step, scores or None), the EMAs)."""
+    ema = ema if ema is not None else Ema(0.0, 0.0, 0.0)
+    log = []
+    for t in range(first_step, first_step + steps):
+        grads = grads_of_step(t)
+        plan, scores = [(st.bm, st.bv) for st in states], None
+        if decide_due(t, U):
+            bm, bv, scores = decide(ema, [grad_stats(g) for g in grads], t, **decide_kw)
+            plan = [(int(a), int(b)) for a, b in zip(bm, bv)]
+        for p, g, st, (bm, bv) in zip(params, grads, states, plan):
+            step_transition(p, g, st, bm, bv, t=t, **hp)
+        log.append((t, plan, scores))
+    return log, ema
 
 
 def loop(params: list, states: list, grads_of_step, steps: int, U: int, hp: dict, decide_kw: dict, ema: Ema = None,

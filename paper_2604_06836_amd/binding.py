@@ -17,6 +17,7 @@ STQ_FLAG_STATS = 1
 STQ_FLAG_STATS_GRAD = 2
 STQ_DECIDE_R_ALG1 = 1
 STQ_DECIDE_NO_DUAL, STQ_DECIDE_NO_TEMPORAL, STQ_DECIDE_NO_SPATIAL = 2, 4, 8
+STQ_ENGINE_ALG1_ORDER = 1
 
 
 class StqError(RuntimeError):
@@ -69,7 +70,7 @@ class Codes(C.Structure):
     _fields_ = [("m_codes", C.c_void_p), ("v_codes", C.c_void_p)]
 
 
-EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_stats",
+EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_grad_stats", "stq_stats",
            "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_step",
            "stq_engine_read", "stq_engine_destroy", "stq_table", "stq_strerror"]
 
@@ -96,6 +97,7 @@ def load_library():
     L.stq_step.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(HParams), vp]
     L.stq_step_transition.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(Bits),
                                       C.POINTER(Codes), C.POINTER(HParams), vp]
+    L.stq_grad_stats.argtypes = [vp, C.POINTER(Tensor), u32, u32, u32, vp]
     L.stq_stats.argtypes = [vp, C.POINTER(LayerStats), u32, vp]
     L.stq_repack.argtypes = [vp, u64, u32, C.c_int, vp, u32, vp, u32, vp]
     L.stq_repack_many.argtypes = [vp, C.POINTER(RepackJob), u32, u32, vp]
@@ -104,7 +106,7 @@ def load_library():
     L.stq_decide_due.argtypes = [u32, u32]
     L.stq_table.argtypes = [C.c_int, u32, C.POINTER(C.c_float), u32]
     L.stq_engine_create.argtypes = [vp, C.POINTER(vp), C.POINTER(Tensor), C.POINTER(Codes), u32, C.POINTER(Bits), u32,
-                                    u32, C.POINTER(DecideCfg), C.POINTER(DecideState), vp]
+                                    u32, C.POINTER(DecideCfg), C.POINTER(DecideState), u32, vp]
     L.stq_engine_step.argtypes = [vp, C.POINTER(HParams), u32, C.POINTER(vp), vp]
     L.stq_engine_read.argtypes = [vp, C.POINTER(Bits), C.POINTER(Bits), C.POINTER(Codes), C.POINTER(C.c_double),
                                   C.POINTER(DecideState), vp]
@@ -219,6 +221,10 @@ class Context:
         _check(self._lib.stq_step_transition(self._h, tensors, len(tensors), plan_old, plan_new, arr,
                                              C.byref(hp), C.c_void_p(stream)), "stq_step_transition")
 
+    def grad_stats(self, tensors, block: int, grad_dtype: int, stream: int = 0):
+        _check(self._lib.stq_grad_stats(self._h, tensors, len(tensors), block, grad_dtype, C.c_void_p(stream)),
+               "stq_grad_stats")
+
     def stats(self, n: int, stream: int = 0):
         out = (LayerStats * n)()
         _check(self._lib.stq_stats(self._h, out, n, C.c_void_p(stream)), "stq_stats")
@@ -238,17 +244,17 @@ class Context:
 
     def engine(self, tensors, second, plan, capacity_bits: int, block: int, *, alpha=0.1, tau=1000.0, phi=7.2,
                eps=1e-12, v_offset=0.0, flags=0, thr=(6.8, 12.0, 24.0), bits=(4, 8, 16, 32),
-               ema: Optional[DecideState] = None, stream: int = 0) -> "Engine":
+               ema: Optional[DecideState] = None, alg1_order: bool = False, stream: int = 0) -> "Engine":
         """stq_engine_create.  second: sequence of (m_ptr, v_ptr), the second code buffer of each state."""
         return Engine(self, tensors, second, plan, capacity_bits, block, alpha=alpha, tau=tau, phi=phi, eps=eps,
-                      v_offset=v_offset, flags=flags, thr=thr, bits=bits, ema=ema, stream=stream)
+                      v_offset=v_offset, flags=flags, thr=thr, bits=bits, ema=ema, alg1_order=alg1_order, stream=stream)
 
 
 class Engine:
     """Owns an stq_engine: the device-resident precision loop.  Close it before its Context."""
 
     def __init__(self, ctx: Context, tensors, second, plan, capacity_bits: int, block: int, *, alpha, tau, phi, eps,
-                 v_offset, flags, thr, bits, ema, stream):
+                 v_offset, flags, thr, bits, ema, alg1_order, stream):
         if len(bits) != len(thr) + 1:
             raise ValueError("bits must have len(thr)+1 entries")
         self._lib, self._ctx, self.n = ctx._lib, ctx, len(tensors)
@@ -261,7 +267,8 @@ class Engine:
             a.m_codes, a.v_codes = m, v
         _check(self._lib.stq_engine_create(ctx._h, C.byref(self._h), tensors, sec, self.n, plan, capacity_bits, block,
                                            C.byref(cfg), C.byref(ema) if ema is not None else None,
-                                           C.c_void_p(stream)), "stq_engine_create")
+                                           STQ_ENGINE_ALG1_ORDER if alg1_order else 0, C.c_void_p(stream)),
+               "stq_engine_create")
 
     def step(self, hp: HParams, update_every: int, grads: Optional[Sequence[int]] = None, stream: int = 0):
         """grads: None, or the addresses of the n gradient buffers to use from this step on (a ctypes

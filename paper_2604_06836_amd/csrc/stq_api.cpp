@@ -269,6 +269,30 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
 
 namespace {
 
+// Index of a device-resident tensor table that holds `descs`: one that already does, else the oldest,
+// overwritten in stream order (after the kernels that read it).
+int resident_table(stq_ctx* ctx, const std::vector<TensorDesc>& descs, hipStream_t s, int* out) {
+  const size_t n = descs.size();
+  int table = -1;
+  for (int k = 0; k < kDescTables && table < 0; ++k)
+    if (ctx->uploaded[k].size() == n && std::memcmp(ctx->uploaded[k].data(), descs.data(), sizeof(TensorDesc) * n) == 0)
+      table = k;
+  if (table < 0) {
+    table = ctx->desc_pos;
+    ctx->desc_pos = (table + 1) % kDescTables;
+    const int k = ctx->ring_pos;
+    ctx->ring_pos = (k + 1) % kRing;
+    if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
+    std::memcpy(ctx->h_stage[k], descs.data(), sizeof(TensorDesc) * n);
+    if (hipMemcpyAsync(ctx->d_desc[table], ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
+      return STQ_EHIP;
+    if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
+    ctx->uploaded[table] = descs;
+  }
+  *out = table;
+  return STQ_OK;
+}
+
 // One launch of the step kernel.  new_plan/new_codes are null for the in-place step.
 int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
               const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
@@ -303,25 +327,8 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   if (!g.ok) return STQ_EHIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  // upload the tensor table unless one of the device-resident tables already holds it (a table is
-  // replaced in stream order, after the kernels that read it)
   int table = -1;
-  for (int k = 0; k < kDescTables && table < 0; ++k)
-    if (ctx->uploaded[k].size() == descs.size() &&
-        std::memcmp(ctx->uploaded[k].data(), descs.data(), sizeof(TensorDesc) * n) == 0)
-      table = k;
-  if (table < 0) {
-    table = ctx->desc_pos;
-    ctx->desc_pos = (table + 1) % kDescTables;
-    const int k = ctx->ring_pos;
-    ctx->ring_pos = (k + 1) % kRing;
-    if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
-    std::memcpy(ctx->h_stage[k], descs.data(), sizeof(TensorDesc) * n);
-    if (hipMemcpyAsync(ctx->d_desc[table], ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
-      return STQ_EHIP;
-    if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
-    ctx->uploaded[table] = descs;
-  }
+  if (int e = resident_table(ctx, descs, s, &table)) return e;
 
   // kernel variant: 0 in place, 1 widths change, 2 some state is (or becomes) 16 or 32 bits wide
   int mode = new_plan ? 1 : 0;
@@ -351,6 +358,24 @@ int stq_step_transition(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, con
                         void* stream) {
   if (!plan_new || !new_codes) return STQ_EINVAL;
   return step_impl(ctx, tensors, n, plan_old, plan_new, new_codes, hp, stream);
+}
+
+int stq_grad_stats(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, uint32_t block, uint32_t grad_dtype,
+                   void* stream) {
+  if (grad_dtype > 1) return STQ_EINVAL;
+  if (!ctx || !tensors || n == 0 || n > ctx->max_tensors) return STQ_EINVAL;
+  std::vector<stq_bits> any(n, stq_bits{8, 8});  // the widths play no part here
+  std::vector<TensorDesc> descs;
+  uint32_t total = 0;
+  if (int e = build_descs(ctx, tensors, n, any.data(), block, true, descs, &total)) return e;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  int table = -1;
+  if (int e = resident_table(ctx, descs, static_cast<hipStream_t>(stream), &table)) return e;
+  if (launch_grad_stats(ctx->d_desc[table], n, total, ctx->d_stats, grad_dtype == 1, grad_stats_groups(ctx->n_cu, total), stream) != 0)
+    return STQ_EHIP;
+  for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
+  return STQ_OK;
 }
 
 int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* stream) {

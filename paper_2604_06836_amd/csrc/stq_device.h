@@ -84,6 +84,8 @@ int launch_step(const StepArgs& a, bool grad_bf16, int stats, int mode, uint32_t
 int launch_zero(const ZeroArgs& a, void* stream);
 int launch_repack(const RepackArgs& a, void* stream);
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream);
+int launch_grad_stats(const TensorDesc* desc, uint32_t n_tensors, uint32_t total_tiles, double* stats, bool grad_bf16,
+                      uint32_t groups, void* stream);
 int launch_fill_zero(uint32_t* p, uint64_t words, void* stream);
 
 }  // namespace stq

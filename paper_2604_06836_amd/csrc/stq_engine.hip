@@ -124,6 +124,7 @@ struct stq_engine {
   uint32_t n = 0, total_tiles = 0, block = 0;
   bool wide = false;      // some state may be 16 or 32 bits wide: the kernel variant that handles them
   bool quarters_ok = true;  // every width the loop can take is a multiple of 4 bits
+  bool alg1_order = false;  // decide from a pass over the gradients before the step, as Algorithm 1 is written
   bool pending = false;   // the table holds widths/destinations that differ from the stored ones
   double tau = 0.0;
   PlanCfg cfg;
@@ -164,9 +165,10 @@ int stq_engine_destroy(stq_engine* e) {
 
 int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors, const stq_codes* second,
                       uint32_t n, const stq_bits* initial_plan, uint32_t capacity_bits, uint32_t block,
-                      const stq_decide_cfg* cfg, const stq_decide_state* ema, void* stream) {
+                      const stq_decide_cfg* cfg, const stq_decide_state* ema, uint32_t flags, void* stream) {
   if (!out) return STQ_EINVAL;
   *out = nullptr;
+  if (flags & ~STQ_ENGINE_ALG1_ORDER) return STQ_EINVAL;
   if (!ctx || !tensors || !second || !initial_plan || !cfg) return STQ_EINVAL;
   if (cfg->n_thr > kMaxThr || (cfg->n_thr > 0 && !cfg->thr) || !cfg->bits) return STQ_EINVAL;
   if (!(cfg->tau > 0.0) || !(cfg->alpha >= 0.0 && cfg->alpha <= 1.0)) return STQ_EINVAL;
@@ -207,6 +209,7 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
   e->block = block;
   e->wide = wide;
   e->quarters_ok = quarters_ok;
+  e->alg1_order = (flags & STQ_ENGINE_ALG1_ORDER) != 0;
   e->tau = cfg->tau;
   std::memset(&e->cfg, 0, sizeof(e->cfg));
   e->cfg.alpha = cfg->alpha; e->cfg.phi = cfg->phi; e->cfg.eps = cfg->eps; e->cfg.v_offset = cfg->v_offset;
@@ -269,15 +272,11 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
   }
   const bool due = stq_decide_due(hp->step, update_every) != 0;
   stq_hparams h = *hp;
-  h.flags = due ? STQ_FLAG_STATS_GRAD : 0u;  // the decision reads the gradient's sums only
-  // kernel variant: the widths in the table differ from the stored ones only in the step after a decision
-  const int mode = e->wide ? 2 : (e->pending ? 1 : 0);
-  if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;
-  if (due || e->pending) {
+  auto plan = [&](bool decide) -> int {
     PlanArgs a;
     a.desc = e->d_desc;
     a.n = e->n;
-    a.decide = due ? 1u : 0u;
+    a.decide = decide ? 1u : 0u;
     a.stats = e->d_stats;
     a.fac = e->d_fac;
     a.ema = e->d_ema;
@@ -287,7 +286,29 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
     a.log_s = std::log2(1.0 + 1.0 / std::cosh(static_cast<double>(hp->step) / e->tau));
     a.cfg = e->cfg;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
-    if (hipGetLastError() != hipSuccess) return STQ_EHIP;
+    return hipGetLastError() == hipSuccess ? STQ_OK : STQ_EHIP;
+  };
+  if (e->alg1_order) {
+    // Algorithm 1 as written: statistics of g_t and Map first, then this step's layer loop at the new widths
+    h.flags = 0u;
+    if (due) {
+      if (launch_grad_stats(e->d_desc, e->n, e->total_tiles, e->d_stats, hp->grad_dtype == 1,
+                            grad_stats_groups(e->ctx->n_cu, e->total_tiles), stream) != 0)
+        return STQ_EHIP;
+      if (int err = plan(true)) return err;
+    }
+    const int mode = e->wide ? 2 : (due ? 1 : 0);
+    if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;
+    if (due) return plan(false);  // the states now are what the step wrote
+    return STQ_OK;
+  }
+  // by-product order: the step gathers the statistics, the decision takes effect in the next step
+  h.flags = due ? STQ_FLAG_STATS_GRAD : 0u;  // the decision reads the gradient's sums only
+  // kernel variant: the widths in the table differ from the stored ones only in the step after a decision
+  const int mode = e->wide ? 2 : (e->pending ? 1 : 0);
+  if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;
+  if (due || e->pending) {
+    if (int err = plan(due)) return err;
     e->pending = due;
   }
   return STQ_OK;

@@ -77,4 +77,10 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
 int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total_tiles, double* d_stats,
                  const stq_hparams* hp, int mode, bool quarters_ok, void* stream);
 
+// Workgroups (of four waves) for the gradient-statistics kernel: at most eight per CU, at least one tile per wave.
+inline uint32_t grad_stats_groups(uint32_t n_cu, uint32_t total_tiles) {
+  const uint64_t need = (static_cast<uint64_t>(total_tiles) + 3) / 4, cap = static_cast<uint64_t>(n_cu) * 8;
+  return static_cast<uint32_t>(need < cap ? need : cap);
+}
+
 }  // namespace stq

@@ -1,5 +1,6 @@
 // Small gfx950 kernels around the quantized Adam step: the initial state m_0 = v_0 = 0 of
-// Algorithm 1, the conversion of stored codes when a layer's bit-width changes, and a fill.
+// Algorithm 1, the conversion of stored codes when a layer's bit-width changes, the statistics of the
+// gradients alone, and a fill.
 // The step kernel itself is in stq_step.hip.
 #include <hip/hip_runtime.h>
 
@@ -191,6 +192,112 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, uint64_t wo
   if (i < words) p[i] = 0u;
 }
 
+// --------------------------------------------------- gradient statistics kernel
+// The per-layer sums the bit-width decision reads (Eq. 2, 3, 8: sum g, sum |g|, sum g^2) and max |g|,
+// from the gradients alone: for the order in which Algorithm 1 is written, where the decision of step t
+// precedes that step's layer loop.  Streams the gradients once (HBM-bound).  Each wave takes one
+// contiguous range of the launch-wide tile order; a lane sums its 32 elements of a tile in fp32, the
+// tile sums go into fp64 lane totals, and a wave adds its totals to the layer's accumulators once per
+// layer it touched.
+__device__ __forceinline__ void flush_grad_stats(double* slot, double s0, double s1, double s2, float mx, int lane) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    s0 += __shfl_xor(s0, o, 64);
+    s1 += __shfl_xor(s1, o, 64);
+    s2 += __shfl_xor(s2, o, 64);
+    mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  }
+  if (lane == 0) {
+    atomicAdd(&slot[kGSum], s0);
+    atomicAdd(&slot[kGAbsSum], s1);
+    atomicAdd(&slot[kGSqSum], s2);
+    // non-negative floats order like their bit patterns
+    atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), __builtin_bit_cast(uint32_t, mx));
+  }
+}
+
+typedef uint32_t gs_u32x2 __attribute__((ext_vector_type(2)));
+typedef float gs_f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void grad_stats_kernel(const TensorDesc* desc, uint32_t n_tensors,
+                                                         uint32_t total_tiles, double* stats) {
+  const int lane = threadIdx.x & 63;
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * 4;
+  const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const uint64_t per_wave = (total_tiles + n_waves - 1) / n_waves;
+  const uint64_t begin = gw * per_wave;
+  const uint64_t end = begin + per_wave < total_tiles ? begin + per_wave : total_tiles;
+  if (begin >= end) return;
+  uint32_t lo = 0, hi = n_tensors - 1;  // last l with tile_begin <= begin
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi + 1) >> 1;
+    if (desc[mid].tile_begin <= static_cast<uint32_t>(begin)) lo = mid; else hi = mid - 1;
+  }
+  uint32_t l = lo;
+  uint32_t t_begin = desc[l].tile_begin, t_count = desc[l].n_tiles;
+  uint64_t numel = desc[l].numel;
+  const void* grad = desc[l].grad;
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+  float mx = 0.0f;
+  for (uint64_t t = begin; t < end; ++t) {
+    if (t >= static_cast<uint64_t>(t_begin) + t_count) {  // t < total_tiles, so a later tensor holds it
+      flush_grad_stats(stats + static_cast<size_t>(l) * kStatSlots, s0, s1, s2, mx, lane);
+      s0 = s1 = s2 = 0.0; mx = 0.0f;
+      do {
+        ++l;
+        t_begin = desc[l].tile_begin; t_count = desc[l].n_tiles;
+      } while (t >= static_cast<uint64_t>(t_begin) + t_count);
+      numel = desc[l].numel;
+      grad = desc[l].grad;
+    }
+    const uint64_t base = (t - t_begin) * kTile;
+    const uint64_t left = numel - base;  // >= 1
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f;
+    float g[32];
+    if (left >= static_cast<uint64_t>(kTile)) {  // a whole tile: eight unconditional loads in flight
+      if (BF16) {
+        gs_u32x2 w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          w[i] = __builtin_nontemporal_load(reinterpret_cast<const gs_u32x2*>(static_cast<const uint16_t*>(grad) + base + 256u * i + 4u * lane));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          g[4 * i] = __builtin_bit_cast(float, w[i].x << 16); g[4 * i + 1] = __builtin_bit_cast(float, w[i].x & 0xFFFF0000u);
+          g[4 * i + 2] = __builtin_bit_cast(float, w[i].y << 16); g[4 * i + 3] = __builtin_bit_cast(float, w[i].y & 0xFFFF0000u);
+        }
+      } else {
+        gs_f32x4 w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          w[i] = __builtin_nontemporal_load(reinterpret_cast<const gs_f32x4*>(static_cast<const float*>(grad) + base + 256u * i + 4u * lane));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { g[4 * i] = w[i].x; g[4 * i + 1] = w[i].y; g[4 * i + 2] = w[i].z; g[4 * i + 3] = w[i].w; }
+      }
+    } else {  // the ragged last tile of a tensor: element by element
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {
+        const uint32_t off = 256u * (k >> 2) + 4u * lane + (k & 3);
+        g[k] = 0.0f;
+        if (off < left)
+          g[k] = BF16 ? __builtin_bit_cast(float, static_cast<uint32_t>(static_cast<const uint16_t*>(grad)[base + off]) << 16)
+                      : static_cast<const float*>(grad)[base + off];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      a0 += g[k];
+      a1 += fabsf(g[k]);
+      a2 = __builtin_fmaf(g[k], g[k], a2);
+      mx = fmaxf(mx, fabsf(g[k]));
+    }
+    s0 += static_cast<double>(a0);
+    s1 += static_cast<double>(a1);
+    s2 += static_cast<double>(a2);
+  }
+  flush_grad_stats(stats + static_cast<size_t>(l) * kStatSlots, s0, s1, s2, mx, lane);
+}
+
 }  // namespace
 
 // -------------------------------------------------------------------- launchers
@@ -210,6 +317,14 @@ int launch_repack(const RepackArgs& a, void* stream) {
 
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream) {
   hipLaunchKernelGGL(repack_many_kernel, dim3(groups), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  return static_cast<int>(hipGetLastError());
+}
+
+int launch_grad_stats(const TensorDesc* desc, uint32_t n_tensors, uint32_t total_tiles, double* stats, bool grad_bf16,
+                      uint32_t groups, void* stream) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (grad_bf16) hipLaunchKernelGGL(grad_stats_kernel<true>, dim3(groups), dim3(256), 0, s, desc, n_tensors, total_tiles, stats);
+  else hipLaunchKernelGGL(grad_stats_kernel<false>, dim3(groups), dim3(256), 0, s, desc, n_tensors, total_tiles, stats);
   return static_cast<int>(hipGetLastError());
 }
 

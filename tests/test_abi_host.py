@@ -159,9 +159,9 @@ def test_engine_entry_points_reject_null_handles(lib):
     # no device is touched before the handles are checked
     hp = binding.HParams(1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 128, 0, 0)
     out = C.c_void_p()
-    assert lib.stq_engine_create(None, C.byref(out), None, None, 1, None, 8, 128, None, None, None) == -1
+    assert lib.stq_engine_create(None, C.byref(out), None, None, 1, None, 8, 128, None, None, 0, None) == -1
     assert not out.value
-    assert lib.stq_engine_create(None, None, None, None, 1, None, 8, 128, None, None, None) == -1
+    assert lib.stq_engine_create(None, None, None, None, 1, None, 8, 128, None, None, 0, None) == -1
     assert lib.stq_engine_step(None, C.byref(hp), 10, None, None) == -1
     assert lib.stq_engine_read(None, None, None, None, None, None, None) == -1
     assert lib.stq_engine_destroy(None) == -1

@@ -93,13 +93,13 @@ def check_state(oracle, mdl, info, params_ref, states_ref, tag):
 
 
 def run_engine_against_oracle(oracle, ctx, sizes, K, plan, capacity, bf16, U, steps, decide_kw, seed, lo=-5.0, hi=-2.0,
-                              swap_grads=True):
+                              swap_grads=True, alg1=False):
     mdl = Model(ctx, sizes, K, plan, capacity, bf16, seed)
     gen = grads_of_step(sizes, bf16, seed, lo, hi)
     params_ref = [p.copy() for p in mdl.param0]
     states_ref = [oracle.State.zeros(n, K, bm, bv) for n, (bm, bv) in zip(sizes, plan)]
     ema_ref = oracle.Ema(0.0, 0.0, 0.0)
-    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, capacity, K, **decide_kw)
+    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, capacity, K, alg1_order=alg1, **decide_kw)
     thr = decide_kw.get("thr", (6.8, 12.0, 24.0))
     okw = dict(decide_kw)
     if "flags" in okw:
@@ -115,8 +115,13 @@ def run_engine_against_oracle(oracle, ctx, sizes, K, plan, capacity, bf16, U, st
             hp = binding.HParams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], t, K, int(bf16), 0)
             eng.step(hp, U, mdl.grad_ptrs(k) if swap_grads else None)
             info = eng.read()
-            log, nxt, ema_ref = oracle.loop(params_ref, states_ref, lambda _t: g, 1, U, HP, okw, ema=ema_ref, first_step=t,
-                                            next_plan=nxt)
+            if alg1:   # the decision of step t is already in what step t wrote; nothing stays pending
+                log, ema_ref = oracle.loop_alg1_order(params_ref, states_ref, lambda _t: g, 1, U, HP, okw, ema=ema_ref,
+                                                      first_step=t)
+                nxt = log[0][1]
+            else:
+                log, nxt, ema_ref = oracle.loop(params_ref, states_ref, lambda _t: g, 1, U, HP, okw, ema=ema_ref,
+                                                first_step=t, next_plan=nxt)
             tag = f"step {t}"
             check_state(oracle, mdl, info, params_ref, states_ref, tag)
             sc = log[0][2]
@@ -170,6 +175,21 @@ def test_fixed_gradient_buffers_and_multiples_of_four(oracle, ctx):
     kw = dict(alpha=0.3, tau=4.0, thr=(7.2,), bits=(4, 8))
     run_engine_against_oracle(oracle, ctx, SIZES, 128, [(8, 8)] * len(SIZES), 8, False, 5, 11, kw, seed=14,
                               swap_grads=False)
+
+
+@pytest.mark.parametrize("bf16,K", [(False, 128), (True, 64)])
+def test_algorithm1_order(oracle, ctx, bf16, K):
+    # STQ_ENGINE_ALG1_ORDER: statistics of g_t and Map before the layer loop of the same step
+    kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=(2.0, 5.0, 7.5, 10.0, 13.0), bits=(2, 3, 4, 5, 6, 8))
+    seen = run_engine_against_oracle(oracle, ctx, SIZES, K, [(6, 4)] * len(SIZES), 8, bf16, 3, 10, kw, seed=11, alg1=True)
+    assert len(seen) >= 4, seen
+
+
+def test_algorithm1_order_papers_ladder(oracle, ctx):
+    kw = dict(alpha=0.3, tau=50.0)
+    seen = run_engine_against_oracle(oracle, ctx, SIZES, 64, [(16, 16)] * len(SIZES), 32, True, 4, 9, kw, seed=12,
+                                     lo=-6.0, hi=-1.0, alg1=True)
+    assert seen >= {4, 8, 16}, seen
 
 
 def test_more_tensors_than_threads_of_the_decision_kernel(oracle, ctx):

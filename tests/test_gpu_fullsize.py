@@ -157,10 +157,12 @@ def _window_of(oracle, w, codes_m, codes_v, dm, l, lo, n, bm, bv):
     return mw, vw, ms, vs
 
 
-def test_device_resident_loop_at_full_size(oracle):
-    """stq_engine_step on all 388 gpt2-xl tensors, as bench.py --transition engine launches it.  Per step:
-    sampled windows go through the oracle's width-changing step at the widths the engine had decided, and
-    the decision itself is redone by the oracle from float64 reductions of every tensor's gradient."""
+@pytest.mark.parametrize("alg1", [False, True])
+def test_device_resident_loop_at_full_size(oracle, alg1):
+    """stq_engine_step on all 388 gpt2-xl tensors, as bench.py --transition engine launches it (alg1: in
+    Algorithm 1's written order, the decision of step t applied in step t).  Per step: sampled windows go
+    through the oracle's width-changing step at the widths the engine wrote, and the decision itself is
+    redone by the oracle from float64 reductions of every tensor's gradient."""
     from paper_2604_06836_amd import binding
     w = configs.get_workload("gpt2-xl")
     rng = np.random.default_rng(99)
@@ -175,7 +177,7 @@ def test_device_resident_loop_at_full_size(oracle):
     second = [(dm._spare[(l, 0)].data_ptr(), dm._spare[(l, 1)].data_ptr()) for l in range(L)]
     thr, bits = (2.0, 5.0, 7.5, 10.0, 13.0), (2, 3, 4, 5, 6, 8)
     kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=thr, bits=bits)
-    eng = ctx.engine(dm.tensors, second, dm.cplan, 8, w.K, stream=dm.stream, **kw)
+    eng = ctx.engine(dm.tensors, second, dm.cplan, 8, w.K, alg1_order=alg1, stream=dm.stream, **kw)
     ema = oracle.Ema(0.0, 0.0, 0.0)
     windows = sample_windows(w, rng, n_tensors=8, per_tensor=2)
     changed = 0
@@ -194,9 +196,12 @@ def test_device_resident_loop_at_full_size(oracle):
                 before.append((th, g, st))
             eng.step(hparams_of(w, t), 1, None, dm.stream)
             after = eng.read(dm.stream)
-            assert after["stored"] == info["next"], f"step {t}: the step wrote other widths than decided"
+            if not alg1:
+                assert after["stored"] == info["next"], f"step {t}: the step wrote other widths than decided"
+            else:
+                assert after["next"] == after["stored"], f"step {t}: nothing may stay pending"
             for (l, lo, n), (th, g, st) in zip(windows, before):
-                bm, bv = info["next"][l]
+                bm, bv = after["stored"][l]
                 oracle.step_transition(th, g, st, bm, bv, **w.hparams, t=t)
                 cm, cv = (by_ptr[p] for p in after["current"][l])
                 mw, vw, ms, vs = _window_of(oracle, w, cm, cv, dm, l, lo, n, bm, bv)
@@ -219,9 +224,9 @@ def test_device_resident_loop_at_full_size(oracle):
             assert np.allclose(after["ema"], (ema.n_ema, ema.r_ema, ema.v_ema), rtol=1e-6, atol=0), f"step {t} EMAs"
             for l in range(L):
                 near = any(abs(sc[l] - x) < 1e-4 or abs(sc[l] - 0.5 - x) < 1e-4 for x in thr)
-                if not near:
+                if not near:   # by-product order: the widths the next step writes; written order: this step's
                     assert after["next"][l] == (int(bm_o[l]), int(bv_o[l])), f"step {t} tensor {l}: score {sc[l]}"
-            changed += sum(a != b for a, b in zip(after["next"], after["stored"]))
+            changed += sum(a != b for a, b in zip(after["next"], info["stored"]))
         assert changed > L // 4   # widths really moved
     finally:
         eng.close()

@@ -564,3 +564,33 @@ def test_gradient_only_statistics(oracle, ctx, dtype, K):
             assert g.g_absmax == s.g_absmax
             for name in ("m_sum", "m_sq_sum", "m_err_sq", "m_absmax", "v_sum", "v_sq_sum", "v_err_sq", "v_absmax"):
                 assert getattr(g, name) == 0, (t, l, name)
+
+
+# ------------------------------------------------- statistics of the gradients alone
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_grad_stats_pass(oracle, ctx, dtype):
+    # stq_grad_stats: one pass over the gradients, no step; against the oracle's gradient statistics,
+    # ragged tails, a one-element tensor, several tiles per wave; accumulates over two calls
+    sizes = [1, 63, 2048, 2049, 5 * 2048 + 1000, 300_000, 64]
+    w = configs.Workload(96, f"gpass-{dtype}", [(f"t{i}", n) for i, n in enumerate(sizes)], 128, dtype, 2,
+                         "normal_per_tensor")
+    dm = DeviceModel(ctx, w, [(4, 4)] * len(sizes))
+    before = [p.clone() for p in dm.param]
+    want = [oracle.Stats() for _ in sizes]
+    for t in (1, 2):
+        dm.set_grads(t)
+        dm.ctx.grad_stats(dm.tensors, w.K, 1 if dtype == "bf16" else 0, dm.stream)
+        for l in range(len(sizes)):
+            s = oracle.grad_stats(dm.host_grad(l))
+            want[l].count += s.count
+            want[l].g_sum += s.g_sum; want[l].g_abs_sum += s.g_abs_sum; want[l].g_sq_sum += s.g_sq_sum
+            want[l].g_absmax = max(want[l].g_absmax, s.g_absmax)
+    got = dm.ctx.stats(len(sizes), dm.stream)
+    for l, (g, s) in enumerate(zip(got, want)):
+        assert g.count == s.count
+        for name, scale in (("g_sum", s.g_abs_sum), ("g_abs_sum", s.g_abs_sum), ("g_sq_sum", s.g_sq_sum)):
+            assert abs(getattr(g, name) - getattr(s, name)) <= 1e-5 * scale + s.count * 1.2e-38, (l, name)
+        assert g.g_absmax == s.g_absmax
+        assert g.m_sq_sum == 0 and g.v_sq_sum == 0
+    for p, q in zip(dm.param, before):   # nothing but the accumulators was touched
+        assert torch.equal(p, q)

@@ -95,3 +95,57 @@ def test_loop_can_be_resumed_step_by_step(oracle):
     for p, q, s, r in zip(a[0], b[0], a[1], b[1]):
         assert np.array_equal(p.view(np.uint32), q.view(np.uint32))
         assert np.array_equal(s.um, r.um) and np.array_equal(s.cv, r.cv)
+
+
+def test_gradient_statistics_alone(oracle):
+    # against numpy float64, fp32 and bf16 gradients; equal to the statistics the step gathers
+    rng = np.random.default_rng(4)
+    g = (rng.standard_t(3, 5000) * 1e-3).astype(np.float32)
+    s = oracle.grad_stats(g)
+    g64 = g.astype(np.float64)
+    assert s.count == 5000 and s.g_absmax == np.abs(g).max()
+    assert np.isclose(s.g_sum, g64.sum(), rtol=1e-12, atol=1e-18)
+    assert np.isclose(s.g_abs_sum, np.abs(g64).sum(), rtol=1e-12) and np.isclose(s.g_sq_sum, (g64 * g64).sum(), rtol=1e-12)
+    hb = (g.view(np.uint32) >> 16).astype(np.uint16)          # truncation to bf16 is good enough here
+    sb = oracle.grad_stats(hb)
+    gb = (hb.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.isclose(sb.g_abs_sum, np.abs(gb).sum(), rtol=1e-12) and sb.g_absmax == np.abs(gb).max()
+    st = oracle.State.zeros(5000, 128, 6, 6)
+    via_step = oracle.step(np.zeros(5000, np.float32), g, st, **HP, t=1, want_stats=True)
+    got = (via_step.g_sum, via_step.g_abs_sum, via_step.g_sq_sum, via_step.g_absmax, via_step.count)
+    assert got == (s.g_sum, s.g_abs_sum, s.g_sq_sum, s.g_absmax, s.count)
+
+
+def test_algorithm1_order_applies_the_decision_in_the_same_step(oracle):
+    # the written order: Map before the layer loop.  Its plan at step t is what the by-product order
+    # (statistics gathered during the step) writes one step later, as long as both see the same gradients
+    # and EMAs -- so with gradients that do not depend on the state the two logs are shifted copies.
+    K, U = 64, 5
+    kw = dict(thr=(5.0, 7.5, 10.0), bits=(3, 4, 6, 8), alpha=0.3, tau=4.0, v_offset=-0.5)
+    grads = _grads(SIZES, (1e-2, 1e-3, 1e-5), 21)
+    out = []
+    for fn in (oracle.loop_alg1_order, oracle.loop):
+        rng = np.random.default_rng(6)
+        params = [rng.normal(0, 0.02, n).astype(np.float32) for n in SIZES]
+        states = [oracle.State.zeros(n, K, 8, 8) for n in SIZES]
+        res = fn(params, states, grads, 11, U, HP, kw)
+        out.append((res[0], params, states))
+    alg1, delayed = out[0][0], out[1][0]
+    for (t, plan, sc), (_, _, sc_d) in zip(alg1, delayed):
+        assert (sc is None) == (sc_d is None)
+        if sc is not None:
+            assert np.array_equal(sc, sc_d)          # same statistics, same EMAs, same scores
+    for k in range(len(alg1) - 1):
+        assert alg1[k][1] == delayed[k + 1][1]       # ... applied one step earlier
+    assert alg1[0][1] != [(8, 8)] * 3                # step 1 already writes the decided widths
+    # and the first step equals a plain first step at those widths (m_0 = v_0 = 0)
+    rng = np.random.default_rng(6)
+    p0 = [rng.normal(0, 0.02, n).astype(np.float32) for n in SIZES]
+    for p, g, (bm, bv) in zip(p0, grads(1), alg1[0][1]):
+        oracle.step(p, g, oracle.State.zeros(p.size, K, bm, bv), **HP, t=1)
+    rng = np.random.default_rng(6)
+    q0 = [rng.normal(0, 0.02, n).astype(np.float32) for n in SIZES]
+    st0 = [oracle.State.zeros(n, K, 8, 8) for n in SIZES]
+    oracle.loop_alg1_order(q0, st0, grads, 1, U, HP, kw)
+    for p, q in zip(p0, q0):
+        assert np.array_equal(p.view(np.uint32), q.view(np.uint32))
