@@ -110,7 +110,7 @@ def train_quantized(steps, fixed_plan=None, ladder=(4, 8, 8, 8), start=(8, 8)):
     return losses, widths
 
 
-def train_engine(steps, ladder=(4, 8, 16, 32), start=(16, 16)):
+def train_engine(steps, ladder=(4, 8, 16, 32), start=(16, 16), alg1=False):
     """The same loop through stq_engine_*: the host enqueues one call per step and never reads anything back."""
     m = make_model(0)
     params = [p for p in m.parameters()]
@@ -132,7 +132,7 @@ def train_engine(steps, ladder=(4, 8, 16, 32), start=(16, 16)):
     plan = binding.make_plan([start] * L)
     ctx.zero_state(tensors, plan, K, stream)
     eng = ctx.engine(tensors, [(c[2].data_ptr(), c[3].data_ptr()) for c, _ in keep], plan, cap, K,
-                     alpha=0.1, tau=100.0, thr=(6.8, 12.0, 24.0), bits=ladder, stream=stream)
+                     alpha=0.1, tau=100.0, thr=(6.8, 12.0, 24.0), bits=ladder, alg1_order=alg1, stream=stream)
     losses = []
     for t, (x, y) in enumerate(batches(steps, 1), start=1):
         for p in params:
@@ -147,11 +147,13 @@ def train_engine(steps, ladder=(4, 8, 16, 32), start=(16, 16)):
     return [float(x) for x in losses], final
 
 
-def test_device_resident_loop_trains_like_fp32_adamw():
+@pytest.mark.parametrize("alg1", [False, True])
+def test_device_resident_loop_trains_like_fp32_adamw(alg1):
+    # alg1: the decision of step t applied in step t (Algorithm 1's written order) instead of step t+1
     steps = 400
     ref = train_fp32(steps)
     host, _ = train_quantized(steps, ladder=(4, 8, 16, 32), start=(16, 16))
-    dev, final = train_engine(steps)
+    dev, final = train_engine(steps, alg1=alg1)
     tail = lambda xs: float(np.mean(xs[-50:]))
     assert tail(dev) <= 1.25 * tail(ref) + 1e-3, (tail(dev), tail(ref))
     assert abs(tail(dev) - tail(host)) <= 0.05 * tail(host), (tail(dev), tail(host))   # same decisions, same path
