@@ -1,9 +1,12 @@
 """ctypes front end of the CPU oracle (stq_oracle.c).  TEST INFRASTRUCTURE ONLY.
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
-this module.  It holds argument marshalling and nothing of the method itself:
-every number comes out of the plain C in stq_oracle.c, which is compiled here
-with gcc (fp32, no fused multiply-add, no fast-math).
+this module.  It holds argument marshalling, and the outer iteration of
+Algorithm 1 over steps and layers (`loop`: statistics as a by-product of the step,
+decision applied one step later; `loop_alg1_order`: the order as written) as plain
+Python control flow.  Every number comes out of the plain C in stq_oracle.c, which
+is compiled here with gcc (fp32, no fused multiply-add, no fast-math).
+Pins of the loops: tests/test_oracle_loop.py.
 """
 from __future__ import annotations
 
