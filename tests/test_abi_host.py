@@ -165,3 +165,15 @@ def test_engine_entry_points_reject_null_handles(lib):
     assert lib.stq_engine_step(None, C.byref(hp), 10, None, None) == -1
     assert lib.stq_engine_read(None, None, None, None, None, None, None) == -1
     assert lib.stq_engine_destroy(None) == -1
+
+
+def test_header_is_plain_c():
+    # the boundary is a C ABI: the header must compile as C99 on its own
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "stq.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
