@@ -262,8 +262,13 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
 /* Copy the loop's state to the host and synchronise the stream (for checkpoints,
  * logging and tests; not needed to run the loop).  Any output may be NULL.
  * stored[l]: the widths the states of tensor l are held at now; next[l]: the widths the
- * next step will write; current[l]: the buffers that hold the states now; score (n
- * doubles) and *ema: from the last decision. */
+ * next step will write (equal to stored[l] unless a decision of the default order is
+ * waiting to take effect; always equal in STQ_ENGINE_ALG1_ORDER); current[l]: the
+ * buffers that hold the states now; score (n doubles) and *ema: from the last decision.
+ * A checkpoint is stored[], the current buffers' contents, the scale arrays, the
+ * parameters and *ema; stq_engine_create resumes from it (a decision still waiting at
+ * the time of the checkpoint is not carried over: the next decision step repeats it
+ * from fresh statistics). */
 int stq_engine_read(stq_engine* e, stq_bits* stored, stq_bits* next, stq_codes* current,
                     double* score, stq_decide_state* ema, void* hip_stream);
 
