@@ -233,3 +233,43 @@ def test_argument_checks(ctx):
         assert info["current"] == first
     finally:
         eng.close()
+
+
+def test_checkpoint_and_resume(oracle, ctx):
+    # stop after 5 steps, read the loop's state, destroy the engine, create a new one from what was read
+    # (stored widths, the buffers that hold the states, the EMAs) and go on: the oracle's uninterrupted loop
+    # must still be matched step by step
+    K, U, bf16, sizes = 128, 2, False, SIZES
+    kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=(2.0, 5.0, 7.5, 10.0, 13.0), bits=(2, 3, 4, 5, 6, 8))
+    plan = [(6, 4)] * len(sizes)
+    mdl = Model(ctx, sizes, K, plan, 8, bf16, 31)
+    gen = grads_of_step(sizes, bf16, 31)
+    params_ref = [p.copy() for p in mdl.param0]
+    states_ref = [oracle.State.zeros(n, K, bm, bv) for n, (bm, bv) in zip(sizes, plan)]
+    ema_ref = oracle.Ema(0.0, 0.0, 0.0)
+    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, K, alg1_order=True, **kw)
+    try:
+        for t in range(1, 11):
+            if t == 6:   # checkpoint, tear down, resume
+                info = eng.read()
+                eng.close()
+                tensors = binding.make_tensors(
+                    dict(param=p.data_ptr(), grad=g.data_ptr(), numel=n, m_codes=cur[0], m_scales=s[0].data_ptr(),
+                         v_codes=cur[1], v_scales=s[1].data_ptr())
+                    for p, g, n, cur, s in zip(mdl.param, mdl.grad[0], sizes, info["current"], mdl.scales))
+                other = []
+                for c, cur in zip(mdl.codes, info["current"]):
+                    ptrs = [b.data_ptr() for b in c]
+                    m_other = ptrs[2] if cur[0] == ptrs[0] else ptrs[0]
+                    v_other = ptrs[3] if cur[1] == ptrs[1] else ptrs[1]
+                    other.append((m_other, v_other))
+                ema = binding.DecideState(*info["ema"])
+                eng = ctx.engine(tensors, other, binding.make_plan(info["stored"]), 8, K, alg1_order=True, ema=ema, **kw)
+            g = gen(t)
+            mdl.upload_grads(0, g)
+            hp = binding.HParams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], t, K, 0, 0)
+            eng.step(hp, U, mdl.grad_ptrs(0))
+            log, ema_ref = oracle.loop_alg1_order(params_ref, states_ref, lambda _t: g, 1, U, HP, kw, ema=ema_ref, first_step=t)
+            check_state(oracle, mdl, eng.read(), params_ref, states_ref, f"step {t}")
+    finally:
+        eng.close()
