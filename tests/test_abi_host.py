@@ -51,6 +51,21 @@ def test_state_bytes(lib):
     assert e.value.code == -1
 
 
+def test_scale_bytes_match_the_hand_cases(lib):
+    # the library's scale-array size against the hand-derived cases that also pin the oracle's padding
+    n_cases = 0
+    for line in open(os.path.join(ROOT, "tests", "golden", "scale_padding_cases.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        lhs, rhs = line.split("->")
+        numel, K = (int(t) for t in lhs.split())
+        _, stored = (int(t) for t in rhs.split())
+        assert stq.state_bytes(numel, K, 4)[1] == 4 * stored, line
+        n_cases += 1
+    assert n_cases == 7
+
+
 def test_tables_are_bit_identical_to_the_oracles(lib, oracle):
     # the library and the oracle build their tables independently; the codes can only agree
     # bit for bit if the tables do

@@ -64,6 +64,27 @@ def test_layout_hand_placements(oracle):
     assert n_cases == 12
 
 
+def test_scale_padding_hand_cases(oracle):
+    """pad_scales: real entries first and in block order, zeros after, size per the hand cases."""
+    n_cases = 0
+    for line in open(os.path.join(GOLD, "scale_padding_cases.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        lhs, rhs = line.split("->")
+        numel, K = (int(t) for t in lhs.split())
+        real, stored = (int(t) for t in rhs.split())
+        s = np.arange(1, real + 1, dtype=np.float32)  # every real entry non-zero and distinct
+        out = oracle.pad_scales(s, numel, K)
+        assert out.dtype == np.float32 and out.size == stored, line
+        assert np.array_equal(out[:real], s), line
+        assert not out[real:].any(), line
+        # the number of real entries is the number of blocks the oracle's state holds
+        assert oracle.State.zeros(numel, K, 4, 4).sm.size == real, line
+        n_cases += 1
+    assert n_cases == 7
+
+
 @pytest.mark.parametrize("b", BITS)
 @pytest.mark.parametrize("numel", [1, 3, 255, 2048, 2049, 5000])
 def test_pack_roundtrip_and_independent_packer(oracle, b, numel):
