@@ -22,10 +22,41 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
 
-def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2):
-    """The oracle as it stands, one thread, on the first `budget_elems` parameters of the workload."""
+def block_slices(n, K, parts):
+    """Cut [0, n) into at most `parts` contiguous ranges whose boundaries are multiples of K (the
+    quantization blocks are independent of one another, so the step of a range is the step of its blocks)."""
+    blocks = (n + K - 1) // K
+    parts = max(1, min(parts, blocks))
+    per = (blocks + parts - 1) // parts
+    return [(b * K, min(n, (b + per) * K)) for b in range(0, blocks, per)]
+
+
+def state_slice(oracle, st, lo, hi):
+    """The oracle's state of elements [lo, hi) of a tensor (lo a multiple of K): views, no copies."""
+    K = st.K
+    return oracle.State(hi - lo, K, st.bm, st.bv, um=st.um[lo:hi], sm=st.sm[lo // K:(hi + K - 1) // K],
+                        cv=st.cv[lo:hi], sv=st.sv[lo // K:(hi + K - 1) // K])
+
+
+def host_description():
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"os_cpu_count": os.cpu_count(), "cpu_model": model}
+
+
+def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2, max_threads=16):
+    """The oracle as it stands on the first `budget_elems` parameters of the workload: once on one
+    thread, once with every core of the box's share (a thread per contiguous range of blocks, each
+    calling the same C routine; ctypes releases the interpreter lock).  `value` is the all-cores rate."""
     import numpy as np
     import torch
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import stq_oracle as oracle
     oracle.lib()
     sample, acc = [], 0
@@ -35,19 +66,51 @@ def cpu_baseline(w, plan, budget_elems=60_000_000, steps=2):
             break
         sample.append((l, take))
         acc += take
-    data = []
-    for l, n in sample:
-        th = w.gen_param(l)[:n].numpy().copy()
-        g = w.gen_grad(l, 1)[:n]
-        g = g.view(torch.int16).numpy().view(np.uint16).copy() if w.grad_dtype == "bf16" else g.numpy().copy()
-        data.append((th, g, oracle.State.zeros(n, w.K, *plan[l])))
+
+    def fresh():
+        data = []
+        for l, n in sample:
+            th = w.gen_param(l)[:n].numpy().copy()
+            g = w.gen_grad(l, 1)[:n]
+            g = g.view(torch.int16).numpy().view(np.uint16).copy() if w.grad_dtype == "bf16" else g.numpy().copy()
+            data.append((th, g, oracle.State.zeros(n, w.K, *plan[l])))
+        return data
+
+    data = fresh()
     t0 = time.perf_counter()
     for t in range(1, steps + 1):
         for th, g, st in data:
             oracle.step(th, g, st, **w.hparams, t=t)
-    dt = time.perf_counter() - t0
-    return {"value": acc * steps / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d parameters of the workload (%d tensors), %d steps, %.1f s" % (acc, len(sample), steps, dt)}
+    dt1 = time.perf_counter() - t0
+
+    threads = max(1, min(max_threads, os.cpu_count() or 1))
+    data = fresh()
+    jobs = [(th[lo:hi], g[lo:hi], state_slice(oracle, st, lo, hi))
+            for th, g, st in data for lo, hi in block_slices(st.numel, st.K, threads)]
+    par_steps = steps * 4
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        t0 = time.perf_counter()
+        for t in range(1, par_steps + 1):
+            list(ex.map(lambda j: oracle.step(j[0], j[1], j[2], **w.hparams, t=t), jobs))
+        dtn = time.perf_counter() - t0
+    out = {"value": acc * par_steps / dtn, "unit": "params/s", "cores": threads, "kind": "oracle",
+           "sample": "first %d parameters of the workload (%d tensors): %d steps on %d threads over contiguous "
+                     "ranges of blocks in %.1f s; %d steps on one thread in %.1f s"
+                     % (acc, len(sample), par_steps, threads, dtn, steps, dt1),
+           "one_thread_value": acc * steps / dt1}
+    out.update(host_description())
+    return out
+
+
+def kernel_source_hash():
+    """SHA-256 over the sources of the step kernel: stamps the counter-derived figures under profiles/,
+    so that figures taken from another version of the kernel are not reported as this one's."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2604_06836_amd", "csrc")
+    for name in ("stq_step.hip", "stq_device.h", "stq_tables.h", "stq_tables.cpp"):
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def copy_calibration(torch, n=1 << 28, launches=5):
@@ -90,7 +153,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gpt2-small")
+    ap.add_argument("--workload", default="llama7b-slice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--transition", choices=("repack", "fused", "engine", "engine-alg1"), default="repack",
                     help="how a new bit plan takes effect: stq_repack_many before the step (the configurations' "
@@ -122,8 +185,8 @@ def main():
     stq.load_library()  # fails loudly if the HIP library is missing
     w = configs.get_workload(args.workload)
     # default: the configuration's own step count, repeated on the small workloads so that the timed
-    # region lasts tens of milliseconds at least
-    steps = args.steps if args.steps is not None else max(w.steps, min(200, int(2e10 // w.numel)))
+    # region lasts a few hundred milliseconds
+    steps = args.steps if args.steps is not None else max(w.steps, min(200, int(1.5e11 // w.numel)))
     L = len(w.tensors)
     plan = w.initial_plan()
     ctx = stq.Context(0, max(L, 16))
@@ -247,11 +310,20 @@ def main():
                      "kernel_ms_avg": k_avg_ms, "algorithmic_bytes_per_param": bpp,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
+    # Counter-derived figures (HBM bytes per launch, vector-ALU utilisation) come from separate rocprofv3
+    # --pmc runs of this same command, stored under profiles/ with the hash of the kernel sources they
+    # were taken at; figures of another version of the kernel are not reported.
+    src_hash = kernel_source_hash()
+    out["roofline"]["kernel_source_sha256"] = src_hash
     traffic_file = os.path.join(ROOT, "profiles", "step_kernel_traffic.json")
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ("-engine-alg1" if use_engine else "")))
-        if tr:
+        if tr and tr.get("kernel_source_sha256") == src_hash:
             out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
+            if "valu_busy" in tr:
+                out["roofline"]["valu_busy"] = tr["valu_busy"]
+        elif tr:
+            out["roofline"]["traffic_note"] = "profiles/step_kernel_traffic.json holds counters of another version of the kernel (%s)" % tr.get("kernel_source_sha256")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, w.initial_plan())
     ctx.close()
