@@ -39,6 +39,44 @@ def sample_windows(w, rng, n_tensors=10, per_tensor=3, tiles=2):
     return out
 
 
+def coverage_windows(w, rng, whole_below=1 << 20, frac=0.01, tiles=64, whole_budget=40_000_000):
+    """Windows that cover every tensor of the workload: tensors below `whole_below` elements whole (up
+    to `whole_budget` elements in all), of every other tensor its first and last `tiles` tiles (the ragged
+    tail included) and random runs of `tiles` tiles until at least `frac` of the tensor is covered."""
+    out, spent = [], 0
+    for l, (_, n) in enumerate(w.tensors):
+        nt = (n + TILE - 1) // TILE
+        if n <= whole_below and spent + n <= whole_budget:
+            out.append((l, 0, n))
+            spent += n
+            continue
+        want = max(2, int(np.ceil(frac * nt / tiles)))
+        starts = {0, max(0, nt - tiles)}
+        while len(starts) < want:
+            starts.add(int(rng.integers(0, max(1, nt - tiles))))
+        merged_end = -1
+        for t0 in sorted(starts):   # runs may not overlap: each window is compared on its own
+            t0 = max(t0, merged_end)
+            if t0 >= nt:
+                continue
+            lo = t0 * TILE
+            out.append((l, lo, min(tiles * TILE, n - lo)))
+            merged_end = t0 + tiles
+    return out
+
+
+def oracle_threads():
+    import os
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def parallel(fn, items):
+    """fn over items on the machine's cores (the oracle's C routines release the interpreter lock)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=oracle_threads()) as ex:
+        return list(ex.map(fn, items))
+
+
 def window_state(oracle, dm, w, l, lo, n):
     """Host copy of one window of tensor l: params, grads and the unpacked oracle state."""
     bm, bv = dm.plan[l]
@@ -76,25 +114,31 @@ def check_window(oracle, dm, w, l, lo, n, th_ref, st_ref, tag):
 
 @pytest.mark.parametrize("name", ["gpt2-small", "vit-b16", "gpt2-xl", "llama7b-slice"])
 def test_full_size_sampled_parity(oracle, name):
+    """Every tensor of the workload is covered: the small and medium ones whole, at least 1 % of each
+    large one (first, last and random runs of 64 tiles); about 2-4 % of all elements per step."""
     w = configs.get_workload(name)
     rng = np.random.default_rng(1234 + w.cfg)
     plan = w.initial_plan()
     L = len(w.tensors)
     ctx = stq.Context(0, L)
     dm = DeviceModel(ctx, w, plan)
-    windows = sample_windows(w, rng)
+    windows = coverage_windows(w, rng)
+    covered = sum(n for _, _, n in windows)
+    assert covered >= 0.01 * w.numel and {l for l, _, _ in windows} == set(range(L))
+    print(f"{name}: {len(windows)} windows, {covered} of {w.numel} elements per step", flush=True)
     for t in (1, 2, 3):
         dm.set_grads(t)
         want_stats = t == 3
         before = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
         dm.step(t, stats=want_stats)
         torch.cuda.synchronize()
+        parallel(lambda x: oracle.step(x[0], x[1], x[2], **w.hparams, t=t), before)
         for (l, lo, n), (th, g, st) in zip(windows, before):
-            oracle.step(th, g, st, **w.hparams, t=t)
             check_window(oracle, dm, w, l, lo, n, th, st, f"{name} step {t} tensor {l} window {lo}+{n}")
+        print(f"{name}: step {t} compared", flush=True)
         if want_stats:
             gs = ctx.stats(L, dm.stream)
-            for l in sorted({l for l, _, _ in windows}):
+            for l in range(0, L, max(1, L // 24)):
                 g64 = dm.grad[l].double()
                 assert gs[l].count == g64.numel()
                 assert abs(gs[l].g_sq_sum - float((g64 * g64).sum())) <= 1e-5 * float((g64 * g64).sum())
@@ -105,6 +149,119 @@ def test_full_size_sampled_parity(oracle, name):
                 assert gs[l].m_absmax == float(dm.m_scales[l].max())
                 assert gs[l].v_absmax == float(dm.v_scales[l].max())
                 assert gs[l].m_err_sq <= gs[l].m_sq_sum and gs[l].v_err_sq <= gs[l].v_sq_sum
+                del g64
+    ctx.close()
+    del dm
+    torch.cuda.empty_cache()
+
+
+def codes_window(buf, lo, n, b):
+    t0, nt = lo // TILE, (n + TILE - 1) // TILE
+    return buf[t0 * 64 * b:(t0 + nt) * 64 * b].cpu().numpy().view(np.uint32)
+
+
+def test_repack_many_at_full_size(oracle):
+    """stq_repack_many as the gpt2-xl configuration words its step (statistics, decision, re-pack of the
+    changed states, then the step): all 388 tensors, a new plan that changes most states, so one launch of
+    several hundred jobs and more than a million tiles (the kernel's grid-stride loop runs many times and
+    its waves cross job boundaries).  Windows of every job -- whole small tensors, first, last and random
+    runs of tiles of the large ones -- are compared with the oracle's re-pack of the same stored codes; then
+    the step at the new widths is compared as in the test above."""
+    w = configs.get_workload("gpt2-xl")
+    rng = np.random.default_rng(777)
+    L = len(w.tensors)
+    plan = w.initial_plan()
+    ctx = stq.Context(0, L)
+    dm = DeviceModel(ctx, w, plan, spare_width=8)
+    for t in (1, 2):   # two steps, so that the stored codes are not the initial pattern
+        dm.set_grads(t)
+        dm.step(t)
+    torch.cuda.synchronize()
+    # the new plan: every width moves to another member of the configuration's set, except for a few tensors
+    widths = list(w.bits_m)
+    new_plan = []
+    for l, (bm, bv) in enumerate(plan):
+        if l % 9 == 4:
+            new_plan.append((bm, bv))
+        else:
+            new_plan.append((int(rng.choice([b for b in widths if b != bm])), int(rng.choice([b for b in widths if b != bv]))))
+    windows = coverage_windows(w, rng, frac=0.005)
+    jobs_expected = sum((a[0] != b[0]) + (a[1] != b[1]) for a, b in zip(plan, new_plan))
+    tiles_expected = sum(((n + TILE - 1) // TILE) * ((a[0] != b[0]) + (a[1] != b[1]))
+                         for (_, n), a, b in zip(w.tensors, plan, new_plan))
+    assert jobs_expected > 600 and tiles_expected > 1_000_000
+    old_codes = []
+    for l, lo, n in windows:
+        bm, bv = plan[l]
+        old_codes.append((oracle.unpack(codes_window(dm.m_codes[l], lo, n, bm), n, bm),
+                          oracle.unpack(codes_window(dm.v_codes[l], lo, n, bv), n, bv)))
+    assert dm.apply_plan(new_plan) == jobs_expected
+    torch.cuda.synchronize()
+    print(f"re-packed {jobs_expected} states, {tiles_expected} tiles in one launch; {len(windows)} windows", flush=True)
+
+    def expected(i):
+        (l, lo, n), (um, cv) = windows[i], old_codes[i]
+        (bm0, bv0), (bm1, bv1) = plan[l], new_plan[l]
+        em = oracle.pack(oracle.repack(um, 0, bm0, bm1) if bm0 != bm1 else um, bm1)
+        ev = oracle.pack(oracle.repack(cv, 1, bv0, bv1) if bv0 != bv1 else cv, bv1)
+        return em, ev
+
+    exp = parallel(expected, range(len(windows)))
+    for (l, lo, n), (em, ev) in zip(windows, exp):
+        bm1, bv1 = new_plan[l]
+        assert np.array_equal(codes_window(dm.m_codes[l], lo, n, bm1), em), f"tensor {l} window {lo}+{n}: m codes {plan[l][0]}->{bm1}"
+        assert np.array_equal(codes_window(dm.v_codes[l], lo, n, bv1), ev), f"tensor {l} window {lo}+{n}: v codes {plan[l][1]}->{bv1}"
+    # the step that follows, at the new widths, on the re-packed states
+    dm.set_grads(3)
+    before = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
+    dm.step(3, stats=True)
+    torch.cuda.synchronize()
+    parallel(lambda x: oracle.step(x[0], x[1], x[2], **w.hparams, t=3), before)
+    for (l, lo, n), (th, g, st) in zip(windows, before):
+        check_window(oracle, dm, w, l, lo, n, th, st, f"after re-pack: tensor {l} window {lo}+{n}")
+    ctx.close()
+    del dm
+    torch.cuda.empty_cache()
+
+
+def test_switching_widths_every_five_steps_at_full_size(oracle):
+    """The vit-b16 configuration as worded, at full size: 50 tensors, every 5 steps 10 % of them change one
+    state's width through stq_repack_many (DeviceModel.apply_plan), then the step runs at the new widths.
+    Eleven steps (switches before steps 5 and 10).  The oracle follows on windows that cover every tensor:
+    its own re-pack at the switches, its own step every step; codes, scales and parameters are compared
+    after every step."""
+    w = configs.get_workload("vit-b16")
+    rng = np.random.default_rng(4242)
+    L = len(w.tensors)
+    plan = w.initial_plan()
+    ctx = stq.Context(0, L)
+    dm = DeviceModel(ctx, w, plan, spare_width=8)
+    windows = coverage_windows(w, rng, frac=0.01, tiles=32)
+    ref = None
+    switched = 0
+    for t in range(1, 12):
+        dm.set_grads(t)
+        new_plan = w.switch_plan(plan, t)
+        if ref is None:
+            ref = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
+        else:   # the oracle keeps its own state from step to step; only the gradients come from the device
+            for i, (l, lo, n) in enumerate(windows):
+                ref[i] = (ref[i][0], dm.grad[l][lo:lo + n].cpu().numpy().copy(), ref[i][2])
+        if new_plan != plan:
+            switched += dm.apply_plan(new_plan)
+            for (l, lo, n), (th, g, st) in zip(windows, ref):
+                bm1, bv1 = new_plan[l]
+                if bm1 != st.bm:
+                    st.um, st.bm = oracle.repack(st.um, 0, st.bm, bm1), bm1
+                if bv1 != st.bv:
+                    st.cv, st.bv = oracle.repack(st.cv, 1, st.bv, bv1), bv1
+            plan = new_plan
+        dm.step(t)
+        torch.cuda.synchronize()
+        parallel(lambda x: oracle.step(x[0], x[1], x[2], **w.hparams, t=t), ref)
+        for (l, lo, n), (th, g, st) in zip(windows, ref):
+            check_window(oracle, dm, w, l, lo, n, th, st, f"vit-b16 step {t} tensor {l} window {lo}+{n}")
+    assert switched >= 10
     ctx.close()
     del dm
     torch.cuda.empty_cache()

@@ -594,3 +594,23 @@ def test_grad_stats_pass(oracle, ctx, dtype):
         assert g.m_sq_sum == 0 and g.v_sq_sum == 0
     for p, q in zip(dm.param, before):   # nothing but the accumulators was touched
         assert torch.equal(p, q)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_grad_stats_pass_shows_non_finite_gradients(oracle, ctx, dtype):
+    # the documented way to find an overflowed (loss-scaled) gradient before stepping: after a pass over the
+    # gradients the tensor's g_sq_sum is not finite; tensors with finite gradients are not affected
+    sizes = [5000, 2048 * 3 + 7, 640]
+    w = configs.Workload(95, f"gnonfinite-{dtype}", [(f"t{i}", n) for i, n in enumerate(sizes)], 128, dtype, 1,
+                         "normal_per_tensor")
+    dm = DeviceModel(ctx, w, [(4, 4)] * len(sizes))
+    dm.set_grads(1)
+    dm.grad[0][4321] = float("inf")
+    dm.grad[1][2048 * 3 + 6] = float("nan")
+    dm.ctx.grad_stats(dm.tensors, w.K, 1 if dtype == "bf16" else 0, dm.stream)
+    got = dm.ctx.stats(len(sizes), dm.stream)
+    want = [oracle.grad_stats(dm.host_grad(l)) for l in range(len(sizes))]
+    assert not np.isfinite(got[0].g_sq_sum) and not np.isfinite(want[0].g_sq_sum)
+    assert got[0].g_absmax == float("inf") == want[0].g_absmax
+    assert not np.isfinite(got[1].g_sq_sum) and not np.isfinite(want[1].g_sq_sum)
+    assert np.isfinite(got[2].g_sq_sum) and abs(got[2].g_sq_sum - want[2].g_sq_sum) <= 1e-5 * want[2].g_sq_sum

@@ -148,3 +148,22 @@ def test_statistics_match_float64_numpy(oracle):
     # Eq. 2 / Eq. 8 identity: v_l = n_l^2
     n_l = np.sqrt(s.g_sq_sum / n)
     assert abs(s.g_sq_sum / n - n_l ** 2) < 1e-18
+
+
+def test_gradient_statistics_show_non_finite_gradients(oracle):
+    # the precondition of the step is finite gradients; the gradient pass is how a caller finds out
+    g = (np.random.default_rng(3).standard_normal(500) * 1e-3).astype(np.float32)
+    assert np.isfinite(oracle.grad_stats(g).g_sq_sum)
+    for bad in (np.inf, -np.inf, np.nan):
+        h = g.copy()
+        h[123] = bad
+        s = oracle.grad_stats(h)
+        assert not np.isfinite(s.g_sq_sum)
+        if np.isinf(bad):
+            assert s.g_absmax == np.inf
+    # bf16 bit patterns: 0x7F80 = +Inf, 0x7FC0 = NaN
+    hb = np.zeros(64, np.uint16)
+    hb[5] = 0x7F80
+    assert oracle.grad_stats(hb).g_sq_sum == np.inf
+    hb[5] = 0x7FC0
+    assert np.isnan(oracle.grad_stats(hb).g_sq_sum)
