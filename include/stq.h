@@ -18,12 +18,25 @@
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     stq_zero_state, stq_step, stq_step_transition, stq_repack and stq_repack_many
  *     are asynchronous on that stream; stq_stats synchronises it.  stq_step,
- *     stq_step_transition and stq_repack_many upload a small table from pinned host
- *     memory (and may wait for an upload four calls earlier to have finished), so
- *     they cannot be recorded into a HIP graph.  stq_engine_step is asynchronous too;
- *     with grads = NULL it consists of kernel launches only.
+ *     stq_step_transition and stq_grad_stats keep the tensor tables of the last four
+ *     distinct argument sets on the device: a call whose tensors, plan and block size
+ *     equal one of those, on the same stream, is one kernel launch and nothing else
+ *     (no upload, no wait, no allocation).  Any other call, and every stq_repack_many,
+ *     first uploads a small table from pinned host memory and may wait for the upload
+ *     of four calls earlier to have finished; such a call cannot be recorded into a
+ *     HIP graph.  (The step number reaches the kernel as launch arguments, so a
+ *     recorded launch repeats its own step.)  stq_engine_step is asynchronous too; with
+ *     grads = NULL it consists of kernel launches only.
  *   - One context serves one stream at a time.  Calls on one context must not
- *     overlap from several host threads.
+ *     overlap from several host threads.  A context may move to another stream after
+ *     the caller has ordered the new stream behind the old one's work; tensor tables
+ *     are then uploaded again on the new stream.
+ *   - Gradients, parameters and hyper-parameters must be finite.  A non-finite
+ *     gradient makes the codes of its tile meaningless (only the tensors' own
+ *     buffers are written; no address depends on data).  It shows in the statistics:
+ *     g_sq_sum of that tensor is then not finite (Inf or NaN; also for a finite
+ *     gradient whose square overflows fp32), so a loss-scaling caller can run
+ *     stq_grad_stats + stq_stats first and skip the step.
  *
  * Storage of one state (m or v) of a tensor of `numel` elements, block K, width b:
  *   codes : tiles of 2048 elements, 64*b 32-bit words per tile.  Inside a tile,

@@ -13,11 +13,10 @@ using namespace stq;
 
 namespace stq {
 
-int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
-                bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles) {
+int fill_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
+               bool need_param_grad, TensorDesc* out, uint32_t* total_tiles) {
   if (!ctx || !t || !plan || n == 0 || n > ctx->max_tensors) return STQ_EINVAL;
   if (lg_block(K) < 0) return STQ_EBLOCK;
-  out.resize(n);
   uint64_t tiles = 0;
   for (uint32_t l = 0; l < n; ++l) {
     if (int e = check_bits_stored(plan[l].m_bits)) return e;
@@ -51,6 +50,13 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
   }
   *total_tiles = static_cast<uint32_t>(tiles);
   return STQ_OK;
+}
+
+int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
+                bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles) {
+  if (!ctx || n == 0 || n > ctx->max_tensors) return STQ_EINVAL;
+  out.resize(n);
+  return fill_descs(ctx, t, n, plan, K, need_param_grad, out.data(), total_tiles);
 }
 
 }  // namespace stq
@@ -116,6 +122,7 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
   c->device = device;
   c->max_tensors = max_tensors;
   c->n_cu = static_cast<uint32_t>(prop.multiProcessorCount);
+#ifdef STQ_TUNING_ENV  // measurement builds only: launch shape from the environment
   if (const char* e = std::getenv("STQ_GROUPS_PER_CU")) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 8) c->groups_per_cu = static_cast<uint32_t>(v);
@@ -124,6 +131,7 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
     const long v = std::strtol(e, nullptr, 10);
     if (v >= 1 && v <= (1 << 20)) c->chunk_override = static_cast<uint32_t>(v);
   }
+#endif
   DeviceGuard g(device);
   bool ok = g.ok;
   ok = ok && hipMalloc(&c->d_tables, img.size() * 4) == hipSuccess;
@@ -157,6 +165,8 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) { stq_destroy(c); return STQ_EHIP; }
   c->stat_count.assign(max_tensors, 0);
+  c->descs.reserve(max_tensors);
+  for (int k = 0; k < kDescTables; ++k) c->uploaded[k].reserve(max_tensors);
   *out = c;
   return STQ_OK;
 }
@@ -269,35 +279,65 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
 
 namespace {
 
-// Index of a device-resident tensor table that holds `descs`: one that already does, else the oldest,
-// overwritten in stream order (after the kernels that read it).
+// Stage n descriptors (already in pinned slot k, or copied there from `src`) into `dst` in stream order.
+int upload_descs(stq_ctx* ctx, int k, const TensorDesc* src, size_t n, TensorDesc* dst, hipStream_t s) {
+  if (src) std::memcpy(ctx->h_stage[k], src, sizeof(TensorDesc) * n);
+  if (hipMemcpyAsync(dst, ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess) return STQ_EHIP;
+  if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
+  return STQ_OK;
+}
+
+// The next pinned staging slot, free again (its upload of four calls ago has finished).
+int next_stage_slot(stq_ctx* ctx, int* out) {
+  const int k = ctx->ring_pos;
+  if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;
+  ctx->ring_pos = (k + 1) % kRing;
+  *out = k;
+  return STQ_OK;
+}
+
+// Index of a device-resident tensor table that holds `descs`: one that already does (uploaded on this
+// same stream, so the kernel is ordered after the upload), else the oldest, overwritten in stream order
+// (after the kernels that read it).
 int resident_table(stq_ctx* ctx, const std::vector<TensorDesc>& descs, hipStream_t s, int* out) {
   const size_t n = descs.size();
   int table = -1;
   for (int k = 0; k < kDescTables && table < 0; ++k)
-    if (ctx->uploaded[k].size() == n && std::memcmp(ctx->uploaded[k].data(), descs.data(), sizeof(TensorDesc) * n) == 0)
+    if (ctx->uploaded_on[k] == s && ctx->uploaded[k].size() == n &&
+        std::memcmp(ctx->uploaded[k].data(), descs.data(), sizeof(TensorDesc) * n) == 0)
       table = k;
   if (table < 0) {
     table = ctx->desc_pos;
+    int k = -1;
+    if (int e = next_stage_slot(ctx, &k)) return e;
+    ctx->uploaded[table].clear();  // whatever happens below, the old contents are no longer claimed
+    if (int e = upload_descs(ctx, k, descs.data(), n, ctx->d_desc[table], s)) return e;
     ctx->desc_pos = (table + 1) % kDescTables;
-    const int k = ctx->ring_pos;
-    ctx->ring_pos = (k + 1) % kRing;
-    if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
-    std::memcpy(ctx->h_stage[k], descs.data(), sizeof(TensorDesc) * n);
-    if (hipMemcpyAsync(ctx->d_desc[table], ctx->h_stage[k], sizeof(TensorDesc) * n, hipMemcpyHostToDevice, s) != hipSuccess)
-      return STQ_EHIP;
-    if (hipEventRecord(ctx->stage_done[k], s) != hipSuccess) return STQ_EHIP;
     ctx->uploaded[table] = descs;
+    ctx->uploaded_on[table] = s;
   }
   *out = table;
   return STQ_OK;
+}
+
+// Kernel variant for a set of descriptors: 0 in place, 1 widths change, 2 some state is (or becomes)
+// 16 or 32 bits wide; and whether every width keeps quarter tiles word-aligned.
+void classify(const TensorDesc* descs, uint32_t n, bool changes, int* mode, bool* quarters_ok) {
+  *mode = changes ? 1 : 0;
+  *quarters_ok = true;
+  for (uint32_t l = 0; l < n; ++l) {
+    const TensorDesc& d = descs[l];
+    if (is_wide(d.bm) || is_wide(d.bv) || is_wide(d.bm_out) || is_wide(d.bv_out)) *mode = 2;
+    *quarters_ok = *quarters_ok && ((d.bm | d.bv | d.bm_out | d.bv_out) & 3u) == 0;
+  }
 }
 
 // One launch of the step kernel.  new_plan/new_codes are null for the in-place step.
 int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
               const stq_bits* new_plan, const stq_codes* new_codes, const stq_hparams* hp, void* stream) {
   if (int e = check_hparams(hp)) return e;
-  std::vector<TensorDesc> descs;
+  if (!ctx) return STQ_EINVAL;
+  std::vector<TensorDesc>& descs = ctx->descs;  // reserved at stq_init: no allocation per call
   uint32_t total = 0;
   if (int e = build_descs(ctx, tensors, n, plan, hp->block, true, descs, &total)) return e;
   if (new_plan) {
@@ -330,14 +370,9 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
   int table = -1;
   if (int e = resident_table(ctx, descs, s, &table)) return e;
 
-  // kernel variant: 0 in place, 1 widths change, 2 some state is (or becomes) 16 or 32 bits wide
-  int mode = new_plan ? 1 : 0;
-  bool quarters_ok = true;
-  for (uint32_t l = 0; l < n; ++l) {
-    const TensorDesc& d = descs[l];
-    if (is_wide(d.bm) || is_wide(d.bv) || is_wide(d.bm_out) || is_wide(d.bv_out)) mode = 2;
-    quarters_ok = quarters_ok && ((d.bm | d.bv | d.bm_out | d.bv_out) & 3u) == 0;
-  }
+  int mode;
+  bool quarters_ok;
+  classify(descs.data(), n, new_plan != nullptr, &mode, &quarters_ok);
   if (int e = launch_table(ctx, ctx->d_desc[table], n, total, ctx->d_stats, hp, mode, quarters_ok, stream)) return e;
   if ((hp->flags & (STQ_FLAG_STATS | STQ_FLAG_STATS_GRAD)) != 0)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;

@@ -37,6 +37,8 @@ struct stq_ctx {
   int jobs_pos = 0;
   double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
   std::vector<stq::TensorDesc> uploaded[stq::kDescTables];  // what each d_desc currently holds
+  hipStream_t uploaded_on[stq::kDescTables] = {nullptr, nullptr, nullptr, nullptr};  // the stream that uploaded it
+  std::vector<stq::TensorDesc> descs;        // descriptors of the call in progress (capacity max_tensors)
   int desc_pos = 0;                          // next table to replace
   std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
 };
@@ -68,6 +70,8 @@ struct DeviceGuard {  // makes the context's device current for the duration of 
 int check_hparams(const stq_hparams* hp);
 
 // Fills the descriptors of n tensors at the widths of `plan` (new codes in place) and the launch-wide tile count.
+int fill_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
+               bool need_param_grad, TensorDesc* out, uint32_t* total_tiles);
 int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_bits* plan, uint32_t K,
                 bool need_param_grad, std::vector<TensorDesc>& out, uint32_t* total_tiles);
 
