@@ -143,6 +143,15 @@ typedef struct {
  * quantizers and allocates the descriptor and statistics buffers. */
 int stq_init(stq_ctx** out, int device, uint32_t max_tensors);
 
+/* Order in which the step kernel takes the tiles of a launch (results do not depend on it, only speed; the
+ * statistics' sums differ in the last bits as with any other order of addition).  Launches of at least
+ * `ticket_min_tiles` tiles (quarter tiles in very small launches) use the ticket schedule: workgroups draw
+ * runs of neighbouring tiles from a counter in device memory and their waves work on them in step, so the
+ * chip sweeps every array front to back inside one compact window -- worth 10-15 % of bandwidth on
+ * multi-gigabyte workloads, a loss on small ones, where each wave keeps walking its own stripes.
+ * 0 restores the default (about 0.3 G elements); UINT64_MAX never uses tickets.  Host only. */
+int stq_set_schedule(stq_ctx* ctx, uint64_t ticket_min_tiles);
+
 /* Synchronise the device and free everything the context owns. */
 int stq_destroy(stq_ctx* ctx);
 

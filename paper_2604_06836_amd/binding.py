@@ -70,7 +70,7 @@ class Codes(C.Structure):
     _fields_ = [("m_codes", C.c_void_p), ("v_codes", C.c_void_p)]
 
 
-EXPORTS = ["stq_init", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_grad_stats", "stq_stats",
+EXPORTS = ["stq_init", "stq_set_schedule", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_grad_stats", "stq_stats",
            "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_step",
            "stq_engine_read", "stq_engine_destroy", "stq_table", "stq_strerror"]
 
@@ -91,6 +91,7 @@ def load_library():
     L = C.CDLL(_LIB_PATH)
     vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
     L.stq_init.argtypes = [C.POINTER(vp), C.c_int, u32]
+    L.stq_set_schedule.argtypes = [vp, u64]
     L.stq_destroy.argtypes = [vp]
     L.stq_state_bytes.argtypes = [u64, u32, u32, C.POINTER(u64), C.POINTER(u64)]
     L.stq_zero_state.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), u32, vp]
@@ -204,6 +205,9 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_schedule(self, ticket_min_tiles: int):
+        _check(self._lib.stq_set_schedule(self._h, ticket_min_tiles), "stq_set_schedule")
 
     def zero_state(self, tensors, plan, block: int, stream: int = 0):
         _check(self._lib.stq_zero_state(self._h, tensors, len(tensors), plan, block, C.c_void_p(stream)),

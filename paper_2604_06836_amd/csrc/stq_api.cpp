@@ -138,6 +138,8 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
   for (int k = 0; k < kDescTables && ok; ++k)
     ok = ok && hipMalloc(&c->d_desc[k], sizeof(TensorDesc) * max_tensors) == hipSuccess;
   ok = ok && hipMalloc(&c->d_stats, sizeof(double) * kStatSlots * max_tensors) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_sched, 256) == hipSuccess;
+  ok = ok && hipMemset(c->d_sched, 0, 256) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_stats, sizeof(double) * kStatSlots * max_tensors, hipHostMallocDefault) == hipSuccess;
   for (int k = 0; k < kRing && ok; ++k) {
     ok = ok && hipHostMalloc(&c->h_stage[k], sizeof(TensorDesc) * max_tensors, hipHostMallocDefault) == hipSuccess;
@@ -171,6 +173,12 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
   return STQ_OK;
 }
 
+int stq_set_schedule(stq_ctx* ctx, uint64_t ticket_min_tiles) {
+  if (!ctx) return STQ_EINVAL;
+  ctx->ticket_min_units = ticket_min_tiles ? ticket_min_tiles : kTicketMinUnits;
+  return STQ_OK;
+}
+
 int stq_destroy(stq_ctx* c) {
   if (!c) return STQ_EINVAL;
   DeviceGuard g(c->device);
@@ -179,6 +187,7 @@ int stq_destroy(stq_ctx* c) {
   for (int k = 0; k < kDescTables; ++k)
     if (c->d_desc[k]) (void)hipFree(c->d_desc[k]);
   if (c->d_stats) (void)hipFree(c->d_stats);
+  if (c->d_sched) (void)hipFree(c->d_sched);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->d_luts) (void)hipFree(c->d_luts);
   if (c->d_jobs) (void)hipFree(c->d_jobs);
@@ -228,7 +237,7 @@ int check_hparams(const stq_hparams* hp) {
 }
 
 int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total, double* d_stats,
-                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream) {
+                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream, uint32_t* sched) {
   StepArgs a;
   a.desc = d_desc;
   a.n_tensors = n;
@@ -272,6 +281,13 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   else if (stats == 2) a.chunk = static_cast<uint32_t>(per_wave >= 64 ? 4 : per_wave);  // its flush is cheap
   else a.chunk = per_wave >= 64 ? 4 : 1;
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
+  // tickets (see step_kernel) for large launches, unless every statistic is collected (that variant keeps one
+  // contiguous range per wave)
+  a.sched = (stats == 1 || units < ctx->ticket_min_units) ? nullptr : (sched ? sched : ctx->d_sched);
+#ifdef STQ_TUNING_ENV
+  if (std::getenv("STQ_NO_TICKETS")) a.sched = nullptr;
+  if (std::getenv("STQ_TICKETS") && stats != 1) a.sched = sched ? sched : ctx->d_sched;
+#endif
   return launch_step(a, hp->grad_dtype == 1, stats, mode, groups, stream) == 0 ? STQ_OK : STQ_EHIP;
 }
 

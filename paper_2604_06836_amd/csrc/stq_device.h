@@ -7,6 +7,7 @@ namespace stq {
 constexpr int kTile = 2048;         // elements per tile = 64 lanes x 32 codes
 constexpr int kWavesPerGroup = 8;   // 512-thread workgroups
 constexpr int kStatSlots = 16;      // 8-byte accumulator slots per tensor
+constexpr uint32_t kSchedWords = 2;  // the ticket counter of a launch and the count of workgroups that have left
 
 // Device-resident description of one tensor for the step kernel.
 struct TensorDesc {
@@ -44,6 +45,9 @@ struct StepArgs {
   uint32_t lgK;            // log2 of the block size: 6, 7 or 8
   uint32_t chunk;          // consecutive units a wave takes at a time, see step_kernel
   uint32_t quarter_units;  // 1: a unit is a quarter tile (small launches whose widths keep quarters word-aligned)
+  uint32_t* sched;         // kSchedWords words, zero between launches: the ticket counters and the count of
+                           // workgroups that have left; null: no tickets, every wave walks its own stripes
+                           // (see step_kernel)
 };
 
 struct ZeroArgs {

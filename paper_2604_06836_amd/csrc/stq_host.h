@@ -13,6 +13,8 @@
 namespace stq {
 
 constexpr int kRing = 4;        // pinned staging slots for descriptor uploads
+constexpr uint64_t kTicketMinUnits = 160000;  // launches of at least this many units draw tickets (see step_kernel):
+                                              // about 0.3 G elements; below, the barrier costs more than the order gains
 constexpr int kDescTables = 4;  // device-resident tensor tables kept: a caller that alternates between a
                                 // few argument sets (two gradient buffers, say) uploads each only once
 
@@ -24,9 +26,11 @@ struct stq_ctx {
   uint32_t n_cu = 0;
   uint32_t groups_per_cu = 3;    // resident workgroups per CU the plain step kernel is launched for
   uint32_t chunk_override = 0;  // tuning aid: STQ_CHUNK in the environment
+  uint64_t ticket_min_units = stq::kTicketMinUnits;  // see stq_set_schedule
   uint32_t* d_tables = nullptr;
   stq::TensorDesc* d_desc[stq::kDescTables] = {nullptr, nullptr, nullptr, nullptr};
   double* d_stats = nullptr;
+  uint32_t* d_sched = nullptr;   // ticket counter and leave count of the step kernel (zero between launches)
   stq::TensorDesc* h_stage[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
   hipEvent_t stage_done[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};
   int ring_pos = 0;
@@ -78,8 +82,9 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
 // Launches the step kernel over the device-resident table `d_desc` of n tensors / total_tiles tiles.
 // mode: 0 in place, 1 widths change, 2 some state is (or may become) 16 or 32 bits wide.
 // quarters_ok: every width of the launch is a multiple of 4 bits.
+// sched: the two scheduling words the launch uses (null: the context's own).
 int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total_tiles, double* d_stats,
-                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream);
+                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream, uint32_t* sched = nullptr);
 
 // Workgroups (of four waves) for the gradient-statistics kernel: at most eight per CU, at least one tile per wave.
 inline uint32_t grad_stats_groups(uint32_t n_cu, uint32_t total_tiles) {

@@ -65,12 +65,21 @@ __device__ __forceinline__ void wave_lds_sync() {
 // ---------------------------------------------------------------- bit streams
 // Within a quarter, code n (0..7) of width B sits at bits [n*B, n*B+B) of the quarter's local stream
 // (at most 64 bits, words w[0], w[1]).
-template <int B>
-__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[3], int n) {
-  const int off = n * B, p = off >> 5, sh = off & 31;
-  constexpr uint32_t mask = (1u << B) - 1u;
-  if (sh + B <= 32) return (w[p] >> sh) & mask;
-  return ((w[p] >> sh) | (w[p + 1] << (32 - sh))) & mask;
+// Bits [SH, SH+B) of x in one instruction.  Written as the instruction itself: from the plain expression
+// the compiler makes a shift and a mask, and then cannot fold the table offset that follows into either.
+template <int SH, int B>
+__device__ __forceinline__ uint32_t bit_field(uint32_t x) {
+  uint32_t r;
+  asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "n"(SH), "n"(B));
+  return r;
+}
+
+template <int B, int N>
+__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[3]) {
+  constexpr int off = N * B, p = off >> 5, sh = off & 31;
+  if (sh + B <= 32) return bit_field<sh, B>(w[p]);
+  // a code that straddles two words: align it first
+  return bit_field<0, B>(__builtin_amdgcn_alignbit(w[p + 1], w[p], static_cast<uint32_t>(sh)));
 }
 
 template <int B>
@@ -89,8 +98,14 @@ __device__ __forceinline__ void unpack_offsets(const uint32_t* lw, uint32_t s0, 
   w[0] = __builtin_amdgcn_alignbit(lw[1], lw[0], s0);
   w[1] = __builtin_amdgcn_alignbit(lw[2], lw[1], s0);
   w[2] = 0u;
-#pragma unroll
-  for (int n = 0; n < 8; ++n) off[n] = (extract<B>(w, n) << 2) | (4u << B);
+  off[0] = (extract<B, 0>(w) << 2) | (4u << B);
+  off[1] = (extract<B, 1>(w) << 2) | (4u << B);
+  off[2] = (extract<B, 2>(w) << 2) | (4u << B);
+  off[3] = (extract<B, 3>(w) << 2) | (4u << B);
+  off[4] = (extract<B, 4>(w) << 2) | (4u << B);
+  off[5] = (extract<B, 5>(w) << 2) | (4u << B);
+  off[6] = (extract<B, 6>(w) << 2) | (4u << B);
+  off[7] = (extract<B, 7>(w) << 2) | (4u << B);
 }
 
 // Pack the 8 codes of a quarter behind the s0 bits that `carry` holds of the current word, store
@@ -233,6 +248,58 @@ __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int l
     for (int k = 0; k < LaneStats<S>::kMaxes; ++k) atomicMax(&out[k], f2u(mx[k]));
   }
   s.clear_all(lane);
+}
+
+// ---- the gradient's statistics under the ticket schedule (S = 2) ----
+// A wave changes tensor with almost every tile there, so it cannot keep sums per tensor.  Instead, after every
+// tile: the wave reduces its four values over its lanes (fp32 tree), adds them (fp64) to the workgroup's
+// accumulator of the current ticket in LDS, and clears its slots.  After the ticket's barrier wave 0 adds the
+// accumulator to the tensor's global slots: one set of atomics per workgroup and ticket.  The accumulator
+// belongs to the tensor of the ticket's first unit; a wave whose tile lies in another tensor (a ticket that
+// straddles a tensor boundary) adds to the global slots itself.
+struct TicketStats {
+  double sum[3];
+  uint32_t max_bits;
+  uint32_t pad;
+};
+static_assert(sizeof(TicketStats) == 32, "layout");
+
+// sum (or maximum) of x over lanes 0..31, valid in lane 0; lanes 32..63 pass zeros
+__device__ __forceinline__ float row_pair_sum(float x) {
+  x += u2f(dpp_u32<kDppXor1>(f2u(x)));
+  x += u2f(dpp_u32<kDppXor2>(f2u(x)));
+  x += u2f(dpp_u32<kDppHalfMirror>(f2u(x)));
+  x += u2f(dpp_u32<kDppMirror>(f2u(x)));
+  return u2f(__builtin_amdgcn_readlane(f2u(x), 0)) + u2f(__builtin_amdgcn_readlane(f2u(x), 16));
+}
+__device__ __forceinline__ uint32_t row_pair_max(uint32_t x) {
+  x = max(x, dpp_u32<kDppXor1>(x));
+  x = max(x, dpp_u32<kDppXor2>(x));
+  x = max(x, dpp_u32<kDppHalfMirror>(x));
+  x = max(x, dpp_u32<kDppMirror>(x));
+  return max(static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 0)), static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 16)));
+}
+
+__device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketStats* wg, bool in_wg_tensor, double* slot, int lane) {
+  float t[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) t[k] = row_pair_sum(lane < 32 ? s.acc[k * 32 + lane] : 0.0f);
+  const uint32_t mx = row_pair_max(lane < 32 ? f2u(s.acc[3 * 32 + lane]) : 0u);
+  if (lane < 32) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s.acc[k * 32 + lane] = 0.0f;
+  }
+  if (lane == 0) {
+    if (in_wg_tensor) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) __hip_atomic_fetch_add(&wg->sum[k], static_cast<double>(t[k]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      __hip_atomic_fetch_max(&wg->max_bits, mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) atomicAdd(&slot[k], static_cast<double>(t[k]));
+      atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
+    }
+  }
 }
 
 // Correctly rounded square root for x = 0 or 2^-96 <= x <= 2^96: the hardware estimate is within
@@ -596,16 +663,27 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   const bool eps_ok = a.eps >= 0x1p-40f && a.eps <= 1.0f;
   bool fast_div;
   if (use_table) {
+    // the scales are in range: the short forms build the table as well (their results are the correctly
+    // rounded ones); else the IEEE routines do, and the quotient later takes the IEEE division too
+    const bool short_forms = eps_ok && !__any(bad_bits);
+    if (!short_forms) bad_bits = 1;
     for (uint32_t e = lane; e < n_entries; e += 64) {
       const uint32_t c = e & ((1u << bvo) - 1u), rg = e >> bvo;
       const uint32_t row = rg >> (8 - lgK), blk = rg & ((1u << (8 - lgK)) - 1u);
       const float sv = SN[((blk << (lgK - 4)) << 2) + 2 + row];
       const float vq = sv * lds_at(Lreg, (c << 2) | l_base);
       const float vt = vq * a.ibc2;
-      const float den = __builtin_sqrtf(vt) + a.eps;
-      const float rden = 1.0f / den;
-      // (plain integer logic: no short-circuit branches)
-      bad_bits |= (static_cast<int>(in_safe_range(den)) & static_cast<int>((f2u(den) & 0x7FFFFFu) != 0x7FFFFFu)) ^ 1;
+      float den, rden;
+      if (short_forms) {
+        den = sqrt_rn_safe(vt) + a.eps;  // vt is 0 or in [2^-80, 2^78]; den in [eps, 2^39 + 1]
+        rden = rcp_rn_safe(den);
+      } else {
+        den = __builtin_sqrtf(vt) + a.eps;
+        rden = 1.0f / den;
+      }
+      // the quotient's short form needs the correctly rounded reciprocal, which a divisor with an all-ones
+      // mantissa may not have
+      bad_bits |= static_cast<int>((f2u(den) & 0x7FFFFFu) == 0x7FFFFFu);
       DEN[e] = make_float2(den, rden);
     }
     fast_div = !__any(bad_bits);
@@ -776,17 +854,31 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 }
 
 // -------------------------------------------------------------- step kernel
-// Tile order: wave w of W takes the chunks w, w+W, w+2W, ... of `chunk` consecutive tiles of the
-// launch-wide tile order.  With a small chunk the waves that run at the same time stream through
-// neighbouring addresses, which the memory system serves best.  The statistics variant flushes
-// its sums once per tensor a wave has touched, so the host gives it one chunk per wave (a
-// contiguous range: few tensors per wave).
+// Order of the work.  A unit is a tile (or a quarter tile, see below).  Two schedules:
+//  * tickets (a.sched set): the workgroups of the launch draw tickets from one counter in device memory.
+//    Ticket k stands for the kWaves consecutive units k*kWaves .. k*kWaves + kWaves-1, one per wave; the
+//    waves of a workgroup meet at a barrier before they go on to the next ticket (drawn while they work on
+//    the current one, so its latency is hidden; a workgroup's first ticket is its own index).  The waves of a
+//    workgroup then read and write neighbouring tiles at the same time, and the chip as a whole works inside
+//    one compact window of the launch-wide order that moves forward in order.  On multi-gigabyte workloads the
+//    memory system gives 10-15 % more bandwidth to this than to waves that each walk their own stripe of the
+//    arrays at their own pace; on small ones the barrier costs more than the order gains.
+//  * stripes (a.sched null): wave w of W takes the chunks w, w+W, w+2W, ... of `chunk` consecutive units.
+//    The variant that collects every statistic uses it with one chunk per wave (a contiguous range: it
+//    flushes its sums once per tensor a wave has touched), small launches with chunk 1.
+// The ticket counter resets itself: the last workgroup to leave the kernel clears it (and the count of
+// workgroups that have left), so every launch -- also a replayed one -- finds both at zero.
 // STATS 1 (all statistics) needs about 30 more registers and 76 KB of LDS: two workgroups per CU.
 // STATS 2 (the gradient's statistics only) stays within the plain kernel's register and LDS budget.
 template <bool BF16, int STATS, int MODE>
 __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + kWavesPerGroup * LaneStats<STATS>::kWords];
+  __shared__ uint32_t drawn[2];  // the ticket being worked on and the next one, alternating
+  __shared__ TicketStats ticket_stats[2];  // gradient statistics of the two tickets in flight (STATS 2 with tickets)
+  if (STATS == 2 && threadIdx.x < 16) reinterpret_cast<uint32_t*>(ticket_stats)[threadIdx.x] = 0u;
+  const bool tickets = a.sched != nullptr;
+  if (threadIdx.x == 0) drawn[0] = blockIdx.x;
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
   __syncthreads();
 
@@ -794,36 +886,55 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* ws = lds + kTabWords + wave * kWaveScratch;
   const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * kWaves;
-  const uint64_t gw = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
   // A unit of scheduling is a tile; in a launch too small to occupy the waves with whole tiles, and
   // whose widths are all multiples of 4 bits (a quarter's codes then start and end on word
   // boundaries), it is a quarter tile.
   const uint32_t qs = a.quarter_units ? 2u : 0u;
   const uint64_t total_units = static_cast<uint64_t>(a.total_tiles) << qs;
   const uint64_t C = a.chunk;
-  uint64_t base = gw * C;
-  if (base >= total_units) return;
+  uint64_t stripe = (static_cast<uint64_t>(blockIdx.x) * kWaves + wave) * C;  // next chunk of this wave (stripes)
+  const uint32_t n_tickets = static_cast<uint32_t>((total_units + kWaves - 1) / kWaves);
+  uint32_t turn = 0;         // which of drawn[] is current (tickets)
+  uint32_t next_ticket = 0;  // thread 0: the ticket drawn for the next round
 
-  // tensor holding the first tile: last l with tile_begin <= tile
-  uint32_t lo = 0, hi = a.n_tensors - 1;
-  while (lo < hi) {
-    const uint32_t mid = (lo + hi + 1) >> 1;
-    if (desc_tile_begin(a.desc, mid) <= static_cast<uint32_t>(base >> qs)) lo = mid; else hi = mid - 1;
-  }
-  uint32_t l = __builtin_amdgcn_readfirstlane(lo);
-  TensorDesc d = load_desc(a.desc, l);
-
+  uint32_t l = 0;
+  bool have_desc = false;
+  TensorDesc d;
   LaneStats<STATS> st;
   st.acc = STATS ? reinterpret_cast<float*>(lds + kLdsWords + wave * LaneStats<STATS>::kWords) : nullptr;
   st.tiles = 0;
   if (STATS) st.clear_all(lane);
-  for (; base < total_units; base += n_waves * C) {
-    const uint64_t c_end = min(base + C, total_units);
-    for (uint64_t u = base; u < c_end; ++u) {
+  for (;;) {
+    uint64_t c_begin, c_end;
+    if (tickets) {
+      const uint32_t cur = __builtin_amdgcn_readfirstlane(drawn[turn]);
+      if (cur >= n_tickets) break;  // the same for every wave of the workgroup
+      // the counter hands out the tickets from gridDim.x on
+      if (threadIdx.x == 0) next_ticket = gridDim.x + __hip_atomic_fetch_add(a.sched, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      c_begin = static_cast<uint64_t>(cur) * kWaves + wave;
+      c_end = min(c_begin + 1, total_units);
+    } else {
+      if (stripe >= total_units) break;
+      c_begin = stripe;
+      c_end = min(stripe + C, total_units);
+      stripe += n_waves * C;
+    }
+    for (uint64_t u = c_begin; u < c_end; ++u) {
       const uint32_t t = static_cast<uint32_t>(u >> qs);
       const uint32_t q_begin = qs ? static_cast<uint32_t>(u & 3u) : 0u, q_end = qs ? q_begin + 1u : 4u;
+      if (!have_desc) {
+        // tensor holding the wave's first tile: last l with tile_begin <= tile
+        uint32_t lo = 0, hi = a.n_tensors - 1;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi + 1) >> 1;
+          if (desc_tile_begin(a.desc, mid) <= t) lo = mid; else hi = mid - 1;
+        }
+        l = __builtin_amdgcn_readfirstlane(lo);
+        d = load_desc(a.desc, l);
+        have_desc = true;
+      }
       if (t >= d.tile_begin + d.n_tiles) {  // t < total_tiles, so a later tensor holds it
-        if (STATS) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+        if (STATS && !(STATS == 2 && tickets)) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
         do {
           ++l;
           d = load_desc(a.desc, l);
@@ -842,10 +953,44 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
           process_quarter<BF16, STATS, true, MODE>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
                                                    carry_v, st);
       }
-      if (STATS && ++st.tiles == kStatFlushTiles) widen_stats(st, lane);
+      if (STATS == 2 && tickets) {
+        if constexpr (STATS == 2) {
+          // does the ticket's first unit lie in this wave's tensor?
+          const uint32_t t_first = static_cast<uint32_t>((c_begin - wave) >> qs);
+          const bool in_wg_tensor = t_first >= d.tile_begin;  // (it cannot lie behind: units only grow)
+          ticket_stats_tile(st, &ticket_stats[turn], in_wg_tensor, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+        }
+      } else if (STATS && ++st.tiles == kStatFlushTiles) {
+        widen_stats(st, lane);
+      }
+    }
+    if (tickets) {
+      if (threadIdx.x == 0) drawn[turn ^ 1u] = next_ticket;
+      __syncthreads();  // the workgroup goes on together
+      if (STATS == 2 && wave == 0 && lane < 4) {
+        // wave 0 worked on the ticket's first unit: l is that unit's tensor
+        TicketStats* wg = &ticket_stats[turn];
+        double* slot = a.stats + static_cast<size_t>(l) * kStatSlots;
+        if (lane < 3) {
+          atomicAdd(&slot[lane], wg->sum[lane]);
+          wg->sum[lane] = 0.0;
+        } else {
+          atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), wg->max_bits);
+          wg->max_bits = 0u;
+        }
+      }
+      turn ^= 1u;
     }
   }
-  if (STATS) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+  if (STATS && !(STATS == 2 && tickets) && have_desc) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+  if (tickets && threadIdx.x == 0) {
+    // every ticket this workgroup drew precedes its leaving; the last one to leave has seen all others leave
+    const uint32_t left_before = __hip_atomic_fetch_add(a.sched + 1, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (left_before == gridDim.x - 1u) {
+      __hip_atomic_store(a.sched, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.sched + 1, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
 }  // namespace

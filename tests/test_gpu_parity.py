@@ -426,26 +426,35 @@ def test_repack_rejects_wide_widths(ctx):
     assert stq.state_bytes(n, 128, 16)[0] == 2 * 64 * 16 * 4 and stq.state_bytes(n, 128, 32)[0] == 2 * 64 * 32 * 4
 
 
-def test_many_small_tensors_in_one_launch(oracle):
-    # 1500 tensors of 1..5000 elements: every wave walks over many tensor boundaries and ragged tiles
+@pytest.mark.parametrize("tickets", [False, True])
+def test_many_small_tensors_in_one_launch(oracle, tickets):
+    # 1500 tensors of 1..5000 elements: every wave walks over many tensor boundaries and ragged tiles;
+    # with the ticket schedule every ticket of eight neighbouring tiles spans several tensors
     rng = np.random.default_rng(77)
     L = 1500
     tensors = [(f"t{i}", int(rng.integers(1, 5001))) for i in range(L)]
     plan = [(int(rng.integers(2, 9)), int(rng.integers(2, 9))) for _ in range(L)]
     w = configs.Workload(130, "many", tensors, 128, "bf16", 2, "normal_per_tensor")
     c = stq.Context(0, L)
+    if tickets:
+        c.set_schedule(1)
     dm = DeviceModel(c, w, plan)
     th_ref = [p.cpu().numpy().copy() for p in dm.param]
     st_ref = oracle_states(oracle, w, plan)
     for t in (1, 2):
         dm.set_grads(t)
-        dm.step(t, stats=(t == 2))
+        dm.step(t, stats=("grad" if tickets else True) if t == 2 else False)
         torch.cuda.synchronize()
         gs = c.stats(L, dm.stream) if t == 2 else None
         for l in range(L):
             s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
-            if gs is not None and l % 13 == 0:
-                assert_stats_close(gs[l], s, f"many tensor {l}")
+            if gs is not None and (l % 13 == 0 or tickets):
+                if tickets:   # the gradient's statistics only
+                    assert abs(gs[l].g_sq_sum - s.g_sq_sum) <= 1e-5 * s.g_sq_sum and gs[l].g_absmax == s.g_absmax, l
+                    assert abs(gs[l].g_abs_sum - s.g_abs_sum) <= 1e-5 * s.g_abs_sum, l
+                    assert abs(gs[l].g_sum - s.g_sum) <= 1e-5 * s.g_abs_sum, l
+                else:
+                    assert_stats_close(gs[l], s, f"many tensor {l}")
     for l in range(L):
         assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"many tensor {l}")
     assert all(gs[l].count == tensors[l][1] for l in range(L))
@@ -453,8 +462,21 @@ def test_many_small_tensors_in_one_launch(oracle):
 
 
 # ---------------------------------------------------------------- seeded random workloads
+@pytest.fixture
+def ticket_ctx(ctx):
+    """The shared context with the ticket schedule forced for every launch, however small."""
+    ctx.set_schedule(1)
+    yield ctx
+    ctx.set_schedule(0)
+
+
 @pytest.mark.parametrize("seed", range(12))
-def test_random_workloads(oracle, ctx, seed):
+def test_random_workloads_ticket_schedule(oracle, ticket_ctx, seed):
+    test_random_workloads(oracle, ticket_ctx, seed, grad_stats_only=True)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_workloads(oracle, ctx, seed, grad_stats_only=False):
     # tensor counts, sizes, block size, gradient type and distribution, widths (quantized and wide),
     # weight decay and the step at which the widths change are all drawn from the seed
     rng = np.random.default_rng(1000 + seed)
@@ -476,6 +498,8 @@ def test_random_workloads(oracle, ctx, seed):
     for t in range(1, 6):
         dm.set_grads(t)
         want_stats = bool(rng.integers(0, 2))
+        if want_stats and grad_stats_only and t % 2 == 0:
+            want_stats = "grad"   # under tickets this variant reduces per ticket and workgroup
         if t == switch_at:
             new = [(int(rng.choice(widths)), int(rng.choice(widths))) for _ in range(L)]
             dm.step_transition(t, new, stats=want_stats)
@@ -490,7 +514,11 @@ def test_random_workloads(oracle, ctx, seed):
             else:
                 s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
             assert_tensor_parity(oracle, dm, l, th_ref[l], st_ref[l], f"{w.name} step {t} tensor {l} {plan[l]}")
-            if want_stats:
+            if want_stats == "grad":
+                assert gs[l].count == s.count and gs[l].g_absmax == s.g_absmax and gs[l].m_sq_sum == 0
+                for name, scale in (("g_sum", s.g_abs_sum), ("g_abs_sum", s.g_abs_sum), ("g_sq_sum", s.g_sq_sum)):
+                    assert abs(getattr(gs[l], name) - getattr(s, name)) <= 1e-5 * scale + s.count * 1.2e-38, (t, l, name)
+            elif want_stats:
                 assert_stats_close(gs[l], s, f"{w.name} step {t} tensor {l}")
         if new is not None:
             plan = new
@@ -533,6 +561,11 @@ def test_argument_checks(ctx):
 
 
 # ------------------------------------------------- the gradient-only statistics flag
+@pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64)])
+def test_gradient_only_statistics_ticket_schedule(oracle, ticket_ctx, dtype, K):
+    test_gradient_only_statistics(oracle, ticket_ctx, dtype, K)
+
+
 @pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64)])
 def test_gradient_only_statistics(oracle, ctx, dtype, K):
     # STQ_FLAG_STATS_GRAD: the step itself is unchanged, the gradient's sums and maximum agree with the
