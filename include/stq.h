@@ -69,7 +69,8 @@ enum {
   STQ_EBLOCK = -4,  /* block size not 64, 128 or 256 */
   STQ_EDEVICE = -5, /* no such device, or not a gfx950 GPU */
   STQ_EHIP = -6,    /* a HIP runtime call failed */
-  STQ_ESTATE = -7   /* stq_stats called with nothing accumulated for that many tensors */
+  STQ_ESTATE = -7,  /* stq_stats called with nothing accumulated for that many tensors */
+  STQ_ELIMIT = -8   /* stq_step_static: more tensors than its static table holds */
 };
 
 typedef struct stq_ctx stq_ctx; /* opaque, owned by the library */
@@ -172,6 +173,21 @@ int stq_zero_state(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
  * read before the call returns.  One kernel launch, no host synchronisation. */
 int stq_step(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
              const stq_bits* bit_plan, const stq_hparams* hp, void* hip_stream);
+
+/* stq_step for callers that cannot allocate device memory or wait for an allocator (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step, the
+ * same kernel and the same results, but the kernel's scratch memory -- the tensor table it reads
+ * and the scheduling words of large launches -- lives in a static device array of the library
+ * (STQ_STATIC_MAX_TENSORS entries of 96 bytes + 256 bytes, about 96 KiB per GPU, held until the
+ * process ends) instead of the context's buffers.  The call allocates nothing on host or device:
+ * it fills a pinned staging slot of the context, copies it to the static table in stream order,
+ * clears the scheduling words with a small kernel and launches.  n above STQ_STATIC_MAX_TENSORS gives STQ_ELIMIT
+ * (n above the context's max_tensors STQ_EINVAL).  Every call on a GPU, from any context, uses
+ * that GPU's one table: calls that overlap on one GPU (two streams, two contexts) race; on one
+ * stream they are ordered.  Statistics flags work as in stq_step (the context's accumulators). */
+#define STQ_STATIC_MAX_TENSORS 1024u
+int stq_step_static(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n,
+                    const stq_bits* bit_plan, const stq_hparams* hp, void* hip_stream);
 
 /* Destination of one tensor's new codes in stq_step_transition. */
 typedef struct {

@@ -70,7 +70,7 @@ class Codes(C.Structure):
     _fields_ = [("m_codes", C.c_void_p), ("v_codes", C.c_void_p)]
 
 
-EXPORTS = ["stq_init", "stq_set_schedule", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_transition", "stq_grad_stats", "stq_stats",
+EXPORTS = ["stq_init", "stq_set_schedule", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_static", "stq_step_transition", "stq_grad_stats", "stq_stats",
            "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_step",
            "stq_engine_read", "stq_engine_destroy", "stq_table", "stq_strerror"]
 
@@ -96,6 +96,7 @@ def load_library():
     L.stq_state_bytes.argtypes = [u64, u32, u32, C.POINTER(u64), C.POINTER(u64)]
     L.stq_zero_state.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), u32, vp]
     L.stq_step.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(HParams), vp]
+    L.stq_step_static.argtypes = L.stq_step.argtypes
     L.stq_step_transition.argtypes = [vp, C.POINTER(Tensor), u32, C.POINTER(Bits), C.POINTER(Bits),
                                       C.POINTER(Codes), C.POINTER(HParams), vp]
     L.stq_grad_stats.argtypes = [vp, C.POINTER(Tensor), u32, u32, u32, vp]
@@ -216,6 +217,10 @@ class Context:
     def step(self, tensors, plan, hp: HParams, stream: int = 0):
         _check(self._lib.stq_step(self._h, tensors, len(tensors), plan, C.byref(hp), C.c_void_p(stream)),
                "stq_step")
+
+    def step_static(self, tensors, plan, hp: HParams, stream: int = 0):
+        _check(self._lib.stq_step_static(self._h, tensors, len(tensors), plan, C.byref(hp), C.c_void_p(stream)),
+               "stq_step_static")
 
     def step_transition(self, tensors, plan_old, plan_new, new_codes, hp: HParams, stream: int = 0):
         """new_codes: sequence of (m_ptr or None, v_ptr or None), one per tensor."""

@@ -61,6 +61,35 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
 
 }  // namespace stq
 
+// ---------------------------------------------------------------- static scratch
+// Device memory of stq_step_static, the entry point that allocates nothing: the tensor table its
+// kernel reads.  One copy per GPU, held until the process ends.  In host code the array's name is only
+// a stand-in for the symbol: the address that kernels and copies use comes from hipGetSymbolAddress,
+// once per device (stq_init), and is kept in g_static_scratch.
+namespace {
+
+constexpr uint32_t kStaticMaxTensors = STQ_STATIC_MAX_TENSORS;
+constexpr size_t kStaticTableBytes = sizeof(TensorDesc) * kStaticMaxTensors;
+constexpr size_t kStaticScratchBytes = kStaticTableBytes + 256;  // the table, then the scheduling words
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices];  // per device, null until a context was created on it
+
+// With `device` current: the address of that device's copy of `scratch`.
+int static_scratch_address(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return STQ_EDEVICE;
+  if (!g_static_scratch[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return STQ_EHIP;
+    g_static_scratch[device] = p;
+  }
+  *out = g_static_scratch[device];
+  return STQ_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* stq_strerror(int code) {
@@ -73,6 +102,7 @@ const char* stq_strerror(int code) {
     case STQ_EDEVICE: return "device missing or not gfx950";
     case STQ_EHIP: return "HIP runtime error";
     case STQ_ESTATE: return "no statistics accumulated";
+    case STQ_ELIMIT: return "more tensors than the static scratch of stq_step_static holds";
     default: return "unknown error";
   }
 }
@@ -134,6 +164,7 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors) {
 #endif
   DeviceGuard g(device);
   bool ok = g.ok;
+  ok = ok && static_scratch_address(device, &c->static_scratch) == STQ_OK;
   ok = ok && hipMalloc(&c->d_tables, img.size() * 4) == hipSuccess;
   for (int k = 0; k < kDescTables && ok; ++k)
     ok = ok && hipMalloc(&c->d_desc[k], sizeof(TensorDesc) * max_tensors) == hipSuccess;
@@ -409,6 +440,35 @@ int stq_step_transition(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, con
                         void* stream) {
   if (!plan_new || !new_codes) return STQ_EINVAL;
   return step_impl(ctx, tensors, n, plan_old, plan_new, new_codes, hp, stream);
+}
+
+int stq_step_static(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bits* plan,
+                    const stq_hparams* hp, void* stream) {
+  if (int e = check_hparams(hp)) return e;
+  if (!ctx || !tensors || !plan || n == 0) return STQ_EINVAL;
+  if (n > kStaticMaxTensors) return STQ_ELIMIT;
+  if (n > ctx->max_tensors) return STQ_EINVAL;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // descriptors straight into a pinned staging slot, from there into this device's static table
+  int k = -1;
+  if (int e = next_stage_slot(ctx, &k)) return e;
+  uint32_t total = 0;
+  if (int e = fill_descs(ctx, tensors, n, plan, hp->block, true, ctx->h_stage[k], &total)) return e;
+  int mode;
+  bool quarters_ok;
+  classify(ctx->h_stage[k], n, false, &mode, &quarters_ok);
+  TensorDesc* table = static_cast<TensorDesc*>(ctx->static_scratch);
+  uint32_t* sched = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ctx->static_scratch) + kStaticTableBytes);
+  if (int e = upload_descs(ctx, k, nullptr, n, table, s)) return e;
+  // the scheduling words must be zero when the kernel starts: a kernel leaves them so, but the array is shared
+  // by every caller on this GPU and may hold what an aborted launch left
+  if (launch_fill_zero(sched, kSchedWords, stream) != 0) return STQ_EHIP;
+  if (int e = launch_table(ctx, table, n, total, ctx->d_stats, hp, mode, quarters_ok, stream, sched)) return e;
+  if ((hp->flags & (STQ_FLAG_STATS | STQ_FLAG_STATS_GRAD)) != 0)
+    for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
+  return STQ_OK;
 }
 
 int stq_grad_stats(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, uint32_t block, uint32_t grad_dtype,

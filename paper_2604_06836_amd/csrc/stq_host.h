@@ -43,6 +43,7 @@ struct stq_ctx {
   std::vector<stq::TensorDesc> uploaded[stq::kDescTables];  // what each d_desc currently holds
   hipStream_t uploaded_on[stq::kDescTables] = {nullptr, nullptr, nullptr, nullptr};  // the stream that uploaded it
   std::vector<stq::TensorDesc> descs;        // descriptors of the call in progress (capacity max_tensors)
+  void* static_scratch = nullptr;            // this device's static table of stq_step_static
   int desc_pos = 0;                          // next table to replace
   std::vector<uint64_t> stat_count;          // elements accumulated per tensor since the last stq_stats
 };
