@@ -252,19 +252,15 @@ __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int l
 
 // ---- the gradient's statistics under the ticket schedule (S = 2) ----
 // A wave changes tensor with almost every tile there, so it cannot keep sums per tensor.  Instead, after every
-// tile: the wave reduces its four values over its lanes (fp32 tree), adds them (fp64) to the workgroup's
-// accumulator of the current ticket in LDS, and clears its slots.  After the ticket's barrier wave 0 adds the
-// accumulator to the tensor's global slots: one set of atomics per workgroup and ticket.  The accumulator
-// belongs to the tensor of the ticket's first unit; a wave whose tile lies in another tensor (a ticket that
-// straddles a tensor boundary) adds to the global slots itself.
-struct TicketStats {
-  double sum[3];
-  uint32_t max_bits;
-  uint32_t pad;
-};
-static_assert(sizeof(TicketStats) == 32, "layout");
+// tile, the wave reduces its four values over its lanes (an fp32 tree), clears its slots and leaves the four
+// values in its record of the current ticket in LDS.  After the ticket's barrier wave 0 adds up the records of
+// the workgroup's waves (fp64) and adds the result to the tensor's global slots: one set of global atomics per
+// workgroup and ticket.  The records belong to the tensor of the ticket's first unit; a wave whose tile lies in
+// another tensor (a ticket that straddles a tensor boundary) adds to that tensor's global slots itself and
+// leaves an empty record.
+struct TicketRecord { float sum[3]; uint32_t max_bits; };
 
-// sum (or maximum) of x over lanes 0..31, valid in lane 0; lanes 32..63 pass zeros
+// sum (maximum) of x over lanes 0..31, which hold the lane pairs' words; lanes 32..63 pass zeros
 __device__ __forceinline__ float row_pair_sum(float x) {
   x += u2f(dpp_u32<kDppXor1>(f2u(x)));
   x += u2f(dpp_u32<kDppXor2>(f2u(x)));
@@ -280,26 +276,40 @@ __device__ __forceinline__ uint32_t row_pair_max(uint32_t x) {
   return max(static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 0)), static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 16)));
 }
 
-__device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketStats* wg, bool in_wg_tensor, double* slot, int lane) {
+// after a tile: the wave's four values -> its record (or, for a straddling tile, the tensor's global slots)
+__device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketRecord* rec, bool in_wg_tensor, double* slot, int lane) {
   float t[3];
 #pragma unroll
   for (int k = 0; k < 3; ++k) t[k] = row_pair_sum(lane < 32 ? s.acc[k * 32 + lane] : 0.0f);
-  const uint32_t mx = row_pair_max(lane < 32 ? f2u(s.acc[3 * 32 + lane]) : 0u);
+  uint32_t mx = row_pair_max(lane < 32 ? f2u(s.acc[3 * 32 + lane]) : 0u);
   if (lane < 32) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) s.acc[k * 32 + lane] = 0.0f;
   }
-  if (lane == 0) {
-    if (in_wg_tensor) {
-#pragma unroll
-      for (int k = 0; k < 3; ++k) __hip_atomic_fetch_add(&wg->sum[k], static_cast<double>(t[k]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      __hip_atomic_fetch_max(&wg->max_bits, mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    } else {
-#pragma unroll
-      for (int k = 0; k < 3; ++k) atomicAdd(&slot[k], static_cast<double>(t[k]));
-      atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
-    }
+  if (!in_wg_tensor) {
+    if (lane < 3) atomicAdd(&slot[lane], static_cast<double>(lane == 0 ? t[0] : (lane == 1 ? t[1] : t[2])));
+    if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
+    t[0] = t[1] = t[2] = 0.0f;
+    mx = 0u;
   }
+  if (lane == 0) *reinterpret_cast<float4*>(rec) = make_float4(t[0], t[1], t[2], u2f(mx));
+}
+
+// wave 0, after the ticket's barrier: the records of the workgroup's waves -> the tensor's global slots
+__device__ __forceinline__ void ticket_stats_flush(const TicketRecord* recs, double* slot, int lane) {
+  static_assert(kWavesPerGroup == 8, "one record per lane of the first eight");
+  const float4 r = *reinterpret_cast<const float4*>(recs + (lane & 7));
+  double t0 = r.x, t1 = r.y, t2 = r.z;
+  uint32_t mx = f2u(r.w);
+#pragma unroll
+  for (int o = 1; o <= 4; o <<= 1) {
+    t0 += __shfl_xor(t0, o, 64);
+    t1 += __shfl_xor(t1, o, 64);
+    t2 += __shfl_xor(t2, o, 64);
+    mx = max(mx, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx), o, 64)));
+  }
+  if (lane < 3) atomicAdd(&slot[lane], lane == 0 ? t0 : (lane == 1 ? t1 : t2));
+  if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
 }
 
 // Correctly rounded square root for x = 0 or 2^-96 <= x <= 2^96: the hardware estimate is within
@@ -875,8 +885,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
   constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + kWavesPerGroup * LaneStats<STATS>::kWords];
   __shared__ uint32_t drawn[2];  // the ticket being worked on and the next one, alternating
-  __shared__ TicketStats ticket_stats[2];  // gradient statistics of the two tickets in flight (STATS 2 with tickets)
-  if (STATS == 2 && threadIdx.x < 16) reinterpret_cast<uint32_t*>(ticket_stats)[threadIdx.x] = 0u;
+  // gradient statistics of the two tickets in flight, one record per wave (STATS 2 with tickets)
+  __shared__ __attribute__((aligned(16))) TicketRecord ticket_rec[2][kWavesPerGroup];
   const bool tickets = a.sched != nullptr;
   if (threadIdx.x == 0) drawn[0] = blockIdx.x;
   for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
@@ -955,29 +965,24 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
       }
       if (STATS == 2 && tickets) {
         if constexpr (STATS == 2) {
-          // does the ticket's first unit lie in this wave's tensor?
+          // does the ticket's first unit lie in this wave's tensor?  (it cannot lie behind it: units only grow)
           const uint32_t t_first = static_cast<uint32_t>((c_begin - wave) >> qs);
-          const bool in_wg_tensor = t_first >= d.tile_begin;  // (it cannot lie behind: units only grow)
-          ticket_stats_tile(st, &ticket_stats[turn], in_wg_tensor, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+          ticket_stats_tile(st, &ticket_rec[turn][wave], t_first >= d.tile_begin, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
         }
       } else if (STATS && ++st.tiles == kStatFlushTiles) {
         widen_stats(st, lane);
       }
     }
     if (tickets) {
+      if constexpr (STATS == 2) {
+        // a wave without a unit in this ticket (the launch's last one) leaves an empty record
+        if (c_begin >= c_end && lane == 0) *reinterpret_cast<float4*>(&ticket_rec[turn][wave]) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      }
       if (threadIdx.x == 0) drawn[turn ^ 1u] = next_ticket;
       __syncthreads();  // the workgroup goes on together
-      if (STATS == 2 && wave == 0 && lane < 4) {
-        // wave 0 worked on the ticket's first unit: l is that unit's tensor
-        TicketStats* wg = &ticket_stats[turn];
-        double* slot = a.stats + static_cast<size_t>(l) * kStatSlots;
-        if (lane < 3) {
-          atomicAdd(&slot[lane], wg->sum[lane]);
-          wg->sum[lane] = 0.0;
-        } else {
-          atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), wg->max_bits);
-          wg->max_bits = 0u;
-        }
+      if constexpr (STATS == 2) {
+        // wave 0 worked on the ticket's first unit: its l is that unit's tensor
+        if (wave == 0) ticket_stats_flush(ticket_rec[turn], a.stats + static_cast<size_t>(l) * kStatSlots, lane);
       }
       turn ^= 1u;
     }
