@@ -221,8 +221,17 @@ def main():
     import ctypes
     grad_ptrs = [(ctypes.c_void_p * L)(*[g.data_ptr() for g in grads[k]]) for k in (0, 1)]
 
+    # The kernel's duration is taken with HIP events around the launches of at most 32 of the timed steps,
+    # evenly spaced: every record of a timing event draws on a pool of the runtime that refills in steps of
+    # tens of milliseconds (seen after about 160 records), which would stall the host inside the timed region.
+    stride = max(1, (steps + 31) // 32)
+    timed_steps = 0
+
     def one_step(t, timed):
-        nonlocal plan, ladder, repacked, pending, engine
+        nonlocal plan, ladder, repacked, pending, engine, timed_steps
+        events = timed and timed_steps % stride == 0
+        if timed:
+            timed_steps += 1
         k = t % 2
         dm.grad = grads[k]
         dm.tensors = tensor_sets[k]
@@ -234,12 +243,13 @@ def main():
                 else:
                     repacked += dm.apply_plan(new_plan, also_patch=(tensor_sets[1 - k],))
                     plan = new_plan
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
+        if events:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
         if engine is not None:
             engine.step(hparams(w, t), 1, grad_ptrs[k], dm.stream)
-            e1.record(stream)
-            if timed:
+            if events:
+                e1.record(stream)
                 kernel_ms.append((e0, e1))
             return
         if pending is not None:
@@ -247,8 +257,8 @@ def main():
             plan, pending = pending, None
         else:
             dm.step(t, stats=stats_arg)
-        e1.record(stream)
-        if timed:
+        if events:
+            e1.record(stream)
             kernel_ms.append((e0, e1))
         if decide_every_step:
             st = ctx.stats(L, dm.stream)

@@ -22,9 +22,9 @@
  *     distinct argument sets on the device: a call whose tensors, plan and block size
  *     equal one of those, on the same stream, is one kernel launch and nothing else
  *     (no upload, no wait, no allocation).  Any other call, and every stq_repack_many,
- *     first uploads a small table from pinned host memory and may wait for the upload
- *     of four calls earlier to have finished; such a call cannot be recorded into a
- *     HIP graph.  (The step number reaches the kernel as launch arguments, so a
+ *     first uploads a small table from pinned host memory (sixteen staging slots
+ *     in turn; a slot whose last upload has not finished yet is waited for); such a
+ *     call cannot be recorded into a HIP graph.  (The step number reaches the kernel as launch arguments, so a
  *     recorded launch repeats its own step.)  stq_engine_step is asynchronous too; with
  *     grads = NULL it consists of kernel launches only.
  *   - One context serves one stream at a time.  Calls on one context must not

@@ -268,7 +268,7 @@ int check_hparams(const stq_hparams* hp) {
 }
 
 int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total, double* d_stats,
-                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream, uint32_t* sched) {
+                 const stq_hparams* hp, int mode, bool quarters_ok, uint32_t v_widths, void* stream, uint32_t* sched) {
   StepArgs a;
   a.desc = d_desc;
   a.n_tensors = n;
@@ -286,6 +286,7 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   a.lr = hp->lr;
   a.decay = 1.0f - hp->lr * hp->weight_decay;
   a.lgK = static_cast<uint32_t>(lg_block(hp->block));
+  a.v_widths = v_widths;
 
   // statistics: all of them, or only the gradient's (the flag for all wins)
   const int stats = (hp->flags & STQ_FLAG_STATS) ? 1 : ((hp->flags & STQ_FLAG_STATS_GRAD) ? 2 : 0);
@@ -334,10 +335,10 @@ int upload_descs(stq_ctx* ctx, int k, const TensorDesc* src, size_t n, TensorDes
   return STQ_OK;
 }
 
-// The next pinned staging slot, free again (its upload of four calls ago has finished).
+// The next pinned staging slot, free again (its upload of kRing calls ago has finished).
 int next_stage_slot(stq_ctx* ctx, int* out) {
   const int k = ctx->ring_pos;
-  if (hipEventSynchronize(ctx->stage_done[k]) != hipSuccess) return STQ_EHIP;
+  if (int e = wait_slot_free(ctx->stage_done[k])) return e;
   ctx->ring_pos = (k + 1) % kRing;
   *out = k;
   return STQ_OK;
@@ -369,11 +370,13 @@ int resident_table(stq_ctx* ctx, const std::vector<TensorDesc>& descs, hipStream
 
 // Kernel variant for a set of descriptors: 0 in place, 1 widths change, 2 some state is (or becomes)
 // 16 or 32 bits wide; and whether every width keeps quarter tiles word-aligned.
-void classify(const TensorDesc* descs, uint32_t n, bool changes, int* mode, bool* quarters_ok) {
+void classify(const TensorDesc* descs, uint32_t n, bool changes, int* mode, bool* quarters_ok, uint32_t* v_widths) {
   *mode = changes ? 1 : 0;
   *quarters_ok = true;
+  *v_widths = 0;
   for (uint32_t l = 0; l < n; ++l) {
     const TensorDesc& d = descs[l];
+    if (d.bv_out <= 8) *v_widths |= 1u << d.bv_out;
     if (is_wide(d.bm) || is_wide(d.bv) || is_wide(d.bm_out) || is_wide(d.bv_out)) *mode = 2;
     *quarters_ok = *quarters_ok && ((d.bm | d.bv | d.bm_out | d.bv_out) & 3u) == 0;
   }
@@ -419,8 +422,9 @@ int step_impl(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const stq_bit
 
   int mode;
   bool quarters_ok;
-  classify(descs.data(), n, new_plan != nullptr, &mode, &quarters_ok);
-  if (int e = launch_table(ctx, ctx->d_desc[table], n, total, ctx->d_stats, hp, mode, quarters_ok, stream)) return e;
+  uint32_t v_widths;
+  classify(descs.data(), n, new_plan != nullptr, &mode, &quarters_ok, &v_widths);
+  if (int e = launch_table(ctx, ctx->d_desc[table], n, total, ctx->d_stats, hp, mode, quarters_ok, v_widths, stream)) return e;
   if ((hp->flags & (STQ_FLAG_STATS | STQ_FLAG_STATS_GRAD)) != 0)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;
@@ -458,14 +462,15 @@ int stq_step_static(stq_ctx* ctx, const stq_tensor* tensors, uint32_t n, const s
   if (int e = fill_descs(ctx, tensors, n, plan, hp->block, true, ctx->h_stage[k], &total)) return e;
   int mode;
   bool quarters_ok;
-  classify(ctx->h_stage[k], n, false, &mode, &quarters_ok);
+  uint32_t v_widths;
+  classify(ctx->h_stage[k], n, false, &mode, &quarters_ok, &v_widths);
   TensorDesc* table = static_cast<TensorDesc*>(ctx->static_scratch);
   uint32_t* sched = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ctx->static_scratch) + kStaticTableBytes);
   if (int e = upload_descs(ctx, k, nullptr, n, table, s)) return e;
   // the scheduling words must be zero when the kernel starts: a kernel leaves them so, but the array is shared
   // by every caller on this GPU and may hold what an aborted launch left
   if (launch_fill_zero(sched, kSchedWords, stream) != 0) return STQ_EHIP;
-  if (int e = launch_table(ctx, table, n, total, ctx->d_stats, hp, mode, quarters_ok, stream, sched)) return e;
+  if (int e = launch_table(ctx, table, n, total, ctx->d_stats, hp, mode, quarters_ok, v_widths, stream, sched)) return e;
   if ((hp->flags & (STQ_FLAG_STATS | STQ_FLAG_STATS_GRAD)) != 0)
     for (uint32_t l = 0; l < n; ++l) ctx->stat_count[l] += tensors[l].numel;
   return STQ_OK;
@@ -575,7 +580,7 @@ int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int k = ctx->jobs_pos;
   ctx->jobs_pos = (k + 1) % kRing;
-  if (hipEventSynchronize(ctx->jobs_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
+  if (int e = wait_slot_free(ctx->jobs_done[k])) return e;
   std::memcpy(ctx->h_jobs[k], table.data(), sizeof(RepackJob) * n);
   if (hipMemcpyAsync(ctx->d_jobs, ctx->h_jobs[k], sizeof(RepackJob) * n, hipMemcpyHostToDevice, s) != hipSuccess)
     return STQ_EHIP;

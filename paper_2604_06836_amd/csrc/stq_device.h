@@ -45,6 +45,7 @@ struct StepArgs {
   uint32_t lgK;            // log2 of the block size: 6, 7 or 8
   uint32_t chunk;          // consecutive units a wave takes at a time, see step_kernel
   uint32_t quarter_units;  // 1: a unit is a quarter tile (small launches whose widths keep quarters word-aligned)
+  uint32_t v_widths;       // bit b set: some second moment may be quantized at width b in this launch
   uint32_t* sched;         // kSchedWords words, zero between launches: the ticket counters and the count of
                            // workgroups that have left; null: no tickets, every wave walks its own stripes
                            // (see step_kernel)

@@ -124,6 +124,7 @@ struct stq_engine {
   uint32_t n = 0, total_tiles = 0, block = 0;
   bool wide = false;      // some state may be 16 or 32 bits wide: the kernel variant that handles them
   bool quarters_ok = true;  // every width the loop can take is a multiple of 4 bits
+  uint32_t v_widths = 0;    // bit b set: a second moment can be quantized at width b (initial plan or the ladder)
   bool alg1_order = false;  // decide from a pass over the gradients before the step, as Algorithm 1 is written
   bool pending = false;   // the table holds widths/destinations that differ from the stored ones
   double tau = 0.0;
@@ -135,8 +136,8 @@ struct stq_engine {
   double* d_score = nullptr;
   uint32_t** d_spare = nullptr;
   const void** d_grads = nullptr;
-  const void** h_grads[kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
-  hipEvent_t grads_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  const void** h_grads[kRing] = {};  // pinned
+  hipEvent_t grads_done[kRing] = {};
   int grads_pos = 0;
   void* h_read = nullptr;  // pinned staging of stq_engine_read
 };
@@ -177,17 +178,20 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
   uint32_t total = 0;
   if (int err = build_descs(ctx, tensors, n, initial_plan, block, true, descs, &total)) return err;
   bool wide = false, quarters_ok = true;
+  uint32_t v_widths = 0;
   for (uint32_t i = 0; i <= cfg->n_thr; ++i) {
     if (int err = check_bits_stored(cfg->bits[i])) return err;
     if (cfg->bits[i] > capacity_bits) return STQ_EINVAL;
     wide = wide || is_wide(cfg->bits[i]);
     quarters_ok = quarters_ok && (cfg->bits[i] & 3u) == 0;
+    if (cfg->bits[i] <= 8) v_widths |= 1u << cfg->bits[i];
   }
   std::vector<uint32_t*> spare(2 * static_cast<size_t>(n));
   for (uint32_t l = 0; l < n; ++l) {
     if (initial_plan[l].m_bits > capacity_bits || initial_plan[l].v_bits > capacity_bits) return STQ_EINVAL;
     wide = wide || is_wide(initial_plan[l].m_bits) || is_wide(initial_plan[l].v_bits);
     quarters_ok = quarters_ok && ((initial_plan[l].m_bits | initial_plan[l].v_bits) & 3u) == 0;
+    if (initial_plan[l].v_bits <= 8) v_widths |= 1u << initial_plan[l].v_bits;
     // the second buffers: distinct from the first over the whole capacity
     const uintptr_t span = static_cast<uintptr_t>(descs[l].n_tiles) * 256 * capacity_bits;
     const void* first[2] = {tensors[l].m_codes, tensors[l].v_codes};
@@ -209,6 +213,7 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
   e->block = block;
   e->wide = wide;
   e->quarters_ok = quarters_ok;
+  e->v_widths = v_widths;
   e->alg1_order = (flags & STQ_ENGINE_ALG1_ORDER) != 0;
   e->tau = cfg->tau;
   std::memset(&e->cfg, 0, sizeof(e->cfg));
@@ -262,7 +267,7 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
   if (grads) {
     const int k = e->grads_pos;
     e->grads_pos = (k + 1) % kRing;
-    if (hipEventSynchronize(e->grads_done[k]) != hipSuccess) return STQ_EHIP;  // slot free again
+    if (int err = wait_slot_free(e->grads_done[k])) return err;
     std::memcpy(e->h_grads[k], grads, sizeof(void*) * e->n);
     if (hipMemcpyAsync(e->d_grads, e->h_grads[k], sizeof(void*) * e->n, hipMemcpyHostToDevice, s) != hipSuccess)
       return STQ_EHIP;
@@ -298,7 +303,7 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
       if (int err = plan(true)) return err;
     }
     const int mode = e->wide ? 2 : (due ? 1 : 0);
-    if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;
+    if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, e->v_widths, stream)) return err;
     if (due) return plan(false);  // the states now are what the step wrote
     return STQ_OK;
   }
@@ -306,7 +311,7 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
   h.flags = due ? STQ_FLAG_STATS_GRAD : 0u;  // the decision reads the gradient's sums only
   // kernel variant: the widths in the table differ from the stored ones only in the step after a decision
   const int mode = e->wide ? 2 : (e->pending ? 1 : 0);
-  if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, stream)) return err;
+  if (int err = launch_table(e->ctx, e->d_desc, e->n, e->total_tiles, e->d_stats, &h, mode, e->quarters_ok, e->v_widths, stream)) return err;
   if (due || e->pending) {
     if (int err = plan(due)) return err;
     e->pending = due;

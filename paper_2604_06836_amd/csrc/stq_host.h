@@ -12,7 +12,7 @@
 
 namespace stq {
 
-constexpr int kRing = 4;        // pinned staging slots for descriptor uploads
+constexpr int kRing = 16;       // pinned staging slots for descriptor uploads
 constexpr uint64_t kTicketMinUnits = 160000;  // launches of at least this many units draw tickets (see step_kernel):
                                               // about 0.3 G elements; below, the barrier costs more than the order gains
 constexpr int kDescTables = 4;  // device-resident tensor tables kept: a caller that alternates between a
@@ -31,13 +31,13 @@ struct stq_ctx {
   stq::TensorDesc* d_desc[stq::kDescTables] = {nullptr, nullptr, nullptr, nullptr};
   double* d_stats = nullptr;
   uint32_t* d_sched = nullptr;   // ticket counter and leave count of the step kernel (zero between launches)
-  stq::TensorDesc* h_stage[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
-  hipEvent_t stage_done[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};
+  stq::TensorDesc* h_stage[stq::kRing] = {};  // pinned
+  hipEvent_t stage_done[stq::kRing] = {};
   int ring_pos = 0;
   uint32_t* d_luts = nullptr;                // every conversion table of the re-pack, kRepackLuts x 256 words
   stq::RepackJob* d_jobs = nullptr;          // 2 * max_tensors
-  stq::RepackJob* h_jobs[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};  // pinned
-  hipEvent_t jobs_done[stq::kRing] = {nullptr, nullptr, nullptr, nullptr};
+  stq::RepackJob* h_jobs[stq::kRing] = {};  // pinned
+  hipEvent_t jobs_done[stq::kRing] = {};
   int jobs_pos = 0;
   double* h_stats = nullptr;                 // pinned, max_tensors * kStatSlots
   std::vector<stq::TensorDesc> uploaded[stq::kDescTables];  // what each d_desc currently holds
@@ -59,6 +59,17 @@ inline int check_bits_stored(uint32_t b) { return (is_wide(b) || check_bits(b) =
 
 inline int lg_block(uint32_t K) {
   switch (K) { case 64: return 6; case 128: return 7; case 256: return 8; default: return -1; }
+}
+
+// A pinned staging slot may be written again once the upload it last fed has finished.  Asking is cheap and
+// almost always enough (the ring is long); waiting is the rare fallback -- on this runtime a wait on an event
+// can take as long as the work queued behind it.
+inline int wait_slot_free(hipEvent_t done) {
+  const hipError_t q = hipEventQuery(done);
+  if (q == hipSuccess) return STQ_OK;
+  if (q != hipErrorNotReady) { (void)hipGetLastError(); return STQ_EHIP; }
+  (void)hipGetLastError();
+  return hipEventSynchronize(done) == hipSuccess ? STQ_OK : STQ_EHIP;
 }
 
 struct DeviceGuard {  // makes the context's device current for the duration of a call
@@ -83,9 +94,11 @@ int build_descs(const stq_ctx* ctx, const stq_tensor* t, uint32_t n, const stq_b
 // Launches the step kernel over the device-resident table `d_desc` of n tensors / total_tiles tiles.
 // mode: 0 in place, 1 widths change, 2 some state is (or may become) 16 or 32 bits wide.
 // quarters_ok: every width of the launch is a multiple of 4 bits.
-// sched: the two scheduling words the launch uses (null: the context's own).
+// v_widths: bit b set if a second moment may be quantized at width b in this launch (the kernel loads the search
+// tables of these widths only).  sched: the two scheduling words the launch uses (null: the context's own).
 int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t total_tiles, double* d_stats,
-                 const stq_hparams* hp, int mode, bool quarters_ok, void* stream, uint32_t* sched = nullptr);
+                 const stq_hparams* hp, int mode, bool quarters_ok, uint32_t v_widths, void* stream,
+                 uint32_t* sched = nullptr);
 
 // Workgroups (of four waves) for the gradient-statistics kernel: at most eight per CU, at least one tile per wave.
 inline uint32_t grad_stats_groups(uint32_t n_cu, uint32_t total_tiles) {

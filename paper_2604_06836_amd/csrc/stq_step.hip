@@ -889,7 +889,13 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
   __shared__ __attribute__((aligned(16))) TicketRecord ticket_rec[2][kWavesPerGroup];
   const bool tickets = a.sched != nullptr;
   if (threadIdx.x == 0) drawn[0] = blockIdx.x;
-  for (int i = threadIdx.x; i < kTabWords; i += 64 * kWaves) lds[i] = a.tables[i];
+  // the value tables of every width (4 KB), the search table of the second-moment widths this launch can write
+  for (int i = threadIdx.x; i < kTabVqOff; i += 64 * kWaves) lds[i] = a.tables[i];
+  for (int b = kMinBits; b <= kMaxBits; ++b) {
+    if (!((a.v_widths >> b) & 1u)) continue;
+    const int base = kTabVqOff + (b - kMinBits) * kVqBuckets * 2;
+    for (int i = threadIdx.x; i < kVqBuckets * 2; i += 64 * kWaves) lds[base + i] = a.tables[base + i];
+  }
   __syncthreads();
 
   const int lane = threadIdx.x & 63;
