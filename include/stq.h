@@ -297,16 +297,23 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
 int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
                     const void* const* grads, void* hip_stream);
 
+/* Carry a waiting decision over a checkpoint (default order only): next[l] (host array of n) are the widths
+ * the engine's first step shall write, i.e. the next[] that stq_engine_read returned when the checkpoint was
+ * taken; the states are still stored at the widths given to stq_engine_create.  Call it between
+ * stq_engine_create and the first stq_engine_step (later, or in STQ_ENGINE_ALG1_ORDER: STQ_ESTATE).  Every
+ * width must be one of the engine's ladder (cfg->bits), else STQ_EINVAL.  Synchronises the stream. */
+int stq_engine_set_next(stq_engine* e, const stq_bits* next, void* hip_stream);
+
 /* Copy the loop's state to the host and synchronise the stream (for checkpoints,
  * logging and tests; not needed to run the loop).  Any output may be NULL.
  * stored[l]: the widths the states of tensor l are held at now; next[l]: the widths the
  * next step will write (equal to stored[l] unless a decision of the default order is
  * waiting to take effect; always equal in STQ_ENGINE_ALG1_ORDER); current[l]: the
  * buffers that hold the states now; score (n doubles) and *ema: from the last decision.
- * A checkpoint is stored[], the current buffers' contents, the scale arrays, the
- * parameters and *ema; stq_engine_create resumes from it (a decision still waiting at
- * the time of the checkpoint is not carried over: the next decision step repeats it
- * from fresh statistics). */
+ * A checkpoint is stored[], next[], the current buffers' contents, the scale arrays, the
+ * parameters and *ema; stq_engine_create resumes from it, and stq_engine_set_next hands it a
+ * decision that was still waiting to take effect when the checkpoint was taken (without it the
+ * resumed loop keeps the stored widths until its next decision step). */
 int stq_engine_read(stq_engine* e, stq_bits* stored, stq_bits* next, stq_codes* current,
                     double* score, stq_decide_state* ema, void* hip_stream);
 

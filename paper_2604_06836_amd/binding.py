@@ -71,7 +71,7 @@ class Codes(C.Structure):
 
 
 EXPORTS = ["stq_init", "stq_set_schedule", "stq_destroy", "stq_state_bytes", "stq_zero_state", "stq_step", "stq_step_static", "stq_step_transition", "stq_grad_stats", "stq_stats",
-           "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_step",
+           "stq_repack", "stq_repack_many", "stq_decide", "stq_decide_due", "stq_engine_create", "stq_engine_set_next", "stq_engine_step",
            "stq_engine_read", "stq_engine_destroy", "stq_table", "stq_strerror"]
 
 _lib = None
@@ -109,6 +109,7 @@ def load_library():
     L.stq_table.argtypes = [C.c_int, u32, C.POINTER(C.c_float), u32]
     L.stq_engine_create.argtypes = [vp, C.POINTER(vp), C.POINTER(Tensor), C.POINTER(Codes), u32, C.POINTER(Bits), u32,
                                     u32, C.POINTER(DecideCfg), C.POINTER(DecideState), u32, vp]
+    L.stq_engine_set_next.argtypes = [vp, C.POINTER(Bits), vp]
     L.stq_engine_step.argtypes = [vp, C.POINTER(HParams), u32, C.POINTER(vp), vp]
     L.stq_engine_read.argtypes = [vp, C.POINTER(Bits), C.POINTER(Bits), C.POINTER(Codes), C.POINTER(C.c_double),
                                   C.POINTER(DecideState), vp]
@@ -286,6 +287,12 @@ class Engine:
             grads = (C.c_void_p * self.n)(*grads)
         _check(self._lib.stq_engine_step(self._h, C.byref(hp), update_every, grads, C.c_void_p(stream)),
                "stq_engine_step")
+
+    def set_next(self, next_plan, stream: int = 0):
+        """stq_engine_set_next: next_plan is a sequence of (m_bits, v_bits) or a ctypes array of Bits."""
+        if not isinstance(next_plan, C.Array):
+            next_plan = make_plan(next_plan)
+        _check(self._lib.stq_engine_set_next(self._h, next_plan, C.c_void_p(stream)), "stq_engine_set_next")
 
     def read(self, stream: int = 0):
         """stq_engine_read: dict with stored and next plans [(m_bits, v_bits)], current code buffers

@@ -126,6 +126,10 @@ struct stq_engine {
   bool quarters_ok = true;  // every width the loop can take is a multiple of 4 bits
   uint32_t v_widths = 0;    // bit b set: a second moment can be quantized at width b (initial plan or the ladder)
   bool alg1_order = false;  // decide from a pass over the gradients before the step, as Algorithm 1 is written
+  bool stepped = false;     // a step has been enqueued
+  uint32_t capacity_bits = 0;
+  std::vector<TensorDesc> h_desc;   // the table as created (for stq_engine_set_next, before the first step)
+  std::vector<uint32_t*> h_spare;
   bool pending = false;   // the table holds widths/destinations that differ from the stored ones
   double tau = 0.0;
   PlanCfg cfg;
@@ -214,6 +218,9 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
   e->wide = wide;
   e->quarters_ok = quarters_ok;
   e->v_widths = v_widths;
+  e->capacity_bits = capacity_bits;
+  e->h_desc = descs;
+  e->h_spare = spare;
   e->alg1_order = (flags & STQ_ENGINE_ALG1_ORDER) != 0;
   e->tau = cfg->tau;
   std::memset(&e->cfg, 0, sizeof(e->cfg));
@@ -251,6 +258,36 @@ int stq_engine_create(stq_ctx* ctx, stq_engine** out, const stq_tensor* tensors,
   return STQ_OK;
 }
 
+int stq_engine_set_next(stq_engine* e, const stq_bits* next, void* stream) {
+  if (!e || !next) return STQ_EINVAL;
+  if (e->stepped || e->alg1_order) return STQ_ESTATE;
+  bool pending = false;
+  std::vector<TensorDesc> descs = e->h_desc;
+  for (uint32_t l = 0; l < e->n; ++l) {
+    TensorDesc& d = descs[l];
+    const uint32_t w[2] = {next[l].m_bits, next[l].v_bits};
+    for (uint32_t b : w) {
+      if (int err = check_bits_stored(b)) return err;
+      bool on_ladder = false;  // a decision of this loop can only have chosen widths of its ladder
+      for (uint32_t i = 0; i <= e->cfg.n_thr; ++i) on_ladder = on_ladder || e->cfg.bits[i] == b;
+      if (!on_ladder || b > e->capacity_bits) return STQ_EINVAL;
+    }
+    d.bm_out = w[0];
+    d.bv_out = w[1];
+    d.m_out = w[0] != d.bm ? e->h_spare[2 * l] : d.m_codes;
+    d.v_out = w[1] != d.bv ? e->h_spare[2 * l + 1] : d.v_codes;
+    pending = pending || w[0] != d.bm || w[1] != d.bv;
+  }
+  DeviceGuard g(e->ctx->device);
+  if (!g.ok) return STQ_EHIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // from pageable host memory: the call returns only after its source was read
+  if (hipMemcpyAsync(e->d_desc, descs.data(), sizeof(TensorDesc) * e->n, hipMemcpyHostToDevice, s) != hipSuccess) return STQ_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return STQ_EHIP;
+  e->pending = pending;
+  return STQ_OK;
+}
+
 int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every, const void* const* grads,
                     void* stream) {
   if (!e) return STQ_EINVAL;
@@ -276,6 +313,7 @@ int stq_engine_step(stq_engine* e, const stq_hparams* hp, uint32_t update_every,
     if (hipGetLastError() != hipSuccess) return STQ_EHIP;
   }
   const bool due = stq_decide_due(hp->step, update_every) != 0;
+  e->stepped = true;
   stq_hparams h = *hp;
   auto plan = [&](bool decide) -> int {
     PlanArgs a;

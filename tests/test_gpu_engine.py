@@ -273,3 +273,68 @@ def test_checkpoint_and_resume(oracle, ctx):
             check_state(oracle, mdl, eng.read(), params_ref, states_ref, f"step {t}")
     finally:
         eng.close()
+
+
+def test_checkpoint_with_a_waiting_decision(oracle, ctx):
+    # default order, a decision every second step: the checkpoint is taken right after a decision step, while
+    # its new widths still wait to take effect.  The resumed engine gets them through stq_engine_set_next and
+    # must go on exactly like the oracle's uninterrupted loop (without them it would keep the old widths
+    # for one more step and diverge).
+    K, U, bf16, sizes = 128, 2, False, SIZES
+    kw = dict(alpha=0.3, tau=4.0, v_offset=-0.5, thr=(2.0, 5.0, 7.5, 10.0, 13.0), bits=(2, 3, 4, 5, 6, 8))
+    plan = [(6, 4)] * len(sizes)
+    mdl = Model(ctx, sizes, K, plan, 8, bf16, 31)
+    gen = grads_of_step(sizes, bf16, 31)
+    params_ref = [p.copy() for p in mdl.param0]
+    states_ref = [oracle.State.zeros(n, K, bm, bv) for n, (bm, bv) in zip(sizes, plan)]
+    ema_ref = oracle.Ema(0.0, 0.0, 0.0)
+    nxt = list(plan)
+    eng = ctx.engine(mdl.tensors, mdl.second, mdl.cplan, 8, K, **kw)
+    waiting_seen = False
+    try:
+        for t in range(1, 12):
+            if t == 7:   # step 6 decided (6 mod 2 = 0): its plan waits for step 7
+                info = eng.read()
+                assert info["next"] == nxt
+                waiting_seen = info["next"] != info["stored"]
+                eng.close()
+                tensors = binding.make_tensors(
+                    dict(param=p.data_ptr(), grad=g.data_ptr(), numel=n, m_codes=cur[0], m_scales=s[0].data_ptr(),
+                         v_codes=cur[1], v_scales=s[1].data_ptr())
+                    for p, g, n, cur, s in zip(mdl.param, mdl.grad[0], sizes, info["current"], mdl.scales))
+                other = []
+                for c, cur in zip(mdl.codes, info["current"]):
+                    ptrs = [b.data_ptr() for b in c]
+                    other.append((ptrs[2] if cur[0] == ptrs[0] else ptrs[0], ptrs[3] if cur[1] == ptrs[1] else ptrs[1]))
+                eng = ctx.engine(tensors, other, binding.make_plan(info["stored"]), 8, K,
+                                 ema=binding.DecideState(*info["ema"]), **kw)
+                with pytest.raises(stq.StqError) as e:   # 7 bits is not on this ladder
+                    eng.set_next([(7, 4)] * len(sizes))
+                assert e.value.code == -1
+                eng.set_next(info["next"])
+                again = eng.read()
+                assert again["stored"] == info["stored"] and again["next"] == info["next"]
+            g = gen(t)
+            mdl.upload_grads(0, g)
+            hp = binding.HParams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], t, K, 0, 0)
+            eng.step(hp, U, mdl.grad_ptrs(0))
+            log, nxt, ema_ref = oracle.loop(params_ref, states_ref, lambda _t: g, 1, U, HP, kw, ema=ema_ref, first_step=t,
+                                            next_plan=nxt)
+            info_t = eng.read()
+            check_state(oracle, mdl, info_t, params_ref, states_ref, f"step {t}")
+            assert info_t["next"] == nxt, f"step {t} next plan"
+        assert waiting_seen, "the checkpoint was meant to catch a waiting decision: pick another seed"
+        with pytest.raises(stq.StqError) as e:   # only before the first step
+            eng.set_next(info_t["next"])
+        assert e.value.code == -7
+    finally:
+        eng.close()
+    # and not at all in Algorithm 1's written order, where nothing ever waits
+    mdl2 = Model(ctx, sizes, K, plan, 8, bf16, 32)
+    eng2 = ctx.engine(mdl2.tensors, mdl2.second, mdl2.cplan, 8, K, alg1_order=True, **kw)
+    try:
+        with pytest.raises(stq.StqError) as e:
+            eng2.set_next(plan)
+        assert e.value.code == -7
+    finally:
+        eng2.close()
