@@ -196,9 +196,8 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, uint64_t wo
 // The per-layer sums the bit-width decision reads (Eq. 2, 3, 8: sum g, sum |g|, sum g^2) and max |g|,
 // from the gradients alone: for the order in which Algorithm 1 is written, where the decision of step t
 // precedes that step's layer loop.  Streams the gradients once (HBM-bound).  Each wave takes one
-// contiguous range of the launch-wide tile order; a lane sums its 32 elements of a tile in fp32, the
-// tile sums go into fp64 lane totals, and a wave adds its totals to the layer's accumulators once per
-// layer it touched.
+// contiguous range of the launch-wide tile order; a lane keeps fp64 totals of its elements, and a wave adds
+// its totals to the layer's accumulators once per layer it touched.
 __device__ __forceinline__ void flush_grad_stats(double* slot, double s0, double s1, double s2, float mx, int lane) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
@@ -253,7 +252,6 @@ __global__ __launch_bounds__(256) void grad_stats_kernel(const TensorDesc* desc,
     }
     const uint64_t base = (t - t_begin) * kTile;
     const uint64_t left = numel - base;  // >= 1
-    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f;
     float g[32];
     if (left >= static_cast<uint64_t>(kTile)) {  // a whole tile: eight unconditional loads in flight
       if (BF16) {
@@ -284,16 +282,16 @@ __global__ __launch_bounds__(256) void grad_stats_kernel(const TensorDesc* desc,
                       : static_cast<const float*>(grad)[base + off];
       }
     }
+    // fp64 from the first addition: the decision compares scores with thresholds, and the variance of Eq. 3
+    // is a difference of two of these sums (the kernel is bound by its one read of the gradients either way)
 #pragma unroll
     for (int k = 0; k < 32; ++k) {
-      a0 += g[k];
-      a1 += fabsf(g[k]);
-      a2 = __builtin_fmaf(g[k], g[k], a2);
+      const double gd = static_cast<double>(g[k]);
+      s0 += gd;
+      s1 += __builtin_fabs(gd);
+      s2 = __builtin_fma(gd, gd, s2);
       mx = fmaxf(mx, fabsf(g[k]));
     }
-    s0 += static_cast<double>(a0);
-    s1 += static_cast<double>(a1);
-    s2 += static_cast<double>(a2);
   }
   flush_grad_stats(stats + static_cast<size_t>(l) * kStatSlots, s0, s1, s2, mx, lane);
 }

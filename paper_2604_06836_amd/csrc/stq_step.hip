@@ -156,59 +156,79 @@ constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16 
 // -------------------------------------------------------------------- statistics
 // (The sums of squares use fused multiply-adds: the fixed operation order binds the Adam
 // arithmetic, not the statistics, which are compared within a tolerance.)
-// Running statistics of one wave, kept in its LDS slice so that they cost no registers between
-// the places that add to them: slot k of lane j is acc[k*64 + j].  Slots 0..8 are fp32 sums of the
-// lane since the last widening, 9..11 running maxima (as bit patterns: all are non-negative)
-// since the last flush; lane k < 9 of slot 12/13 holds the fp64 total of sum k for the current tensor.
-enum LaneSlot { kLGSum = 0, kLGAbs, kLGSq, kLMSum, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr };
-// S = 1: all of the above and the three maxima, in LDS as described.  S = 2: the gradient's three sums
-// and its maximum only (what the bit-width decision consumes).  Neighbouring lanes 2i, 2i+1 first
-// combine their contributions (one DPP operation) and share word i of a 32-word slot -- both write the
-// same value to it -- which keeps the slice small enough for three workgroups per CU and costs no
-// registers: slots 0..2 sums, slot 3 maximum, then the wave's three fp64 totals.
+// Running statistics of one wave, kept in its LDS slice so that they cost no registers between the places
+// that add to them.
+//  * The gradient's three sums (all that the bit-width decision reads, Eq. 2, 3, 8) are taken in fp64 from the
+//    first addition on: fp64 vector additions issue at the rate of fp32 ones here, and a decision that compares a
+//    score with a threshold should not hinge on the rounding of a sum (the variance in Eq. 3 is a difference of
+//    two such sums).  Groups of four neighbouring lanes combine their contributions with two DPP steps and share
+//    one fp64 word of a 16-word slot -- all four write the same value to it; the gradient's maximum likewise in
+//    a 16-word slot of bit patterns (all maxima are non-negative, so they order like their bit patterns).
+//  * S = 1 adds the moments' six fp32 sums and two maxima, one word per lane and slot; their sums since the last
+//    widening are added to fp64 totals (lane k < 6 of the last slot) every kStatFlushTiles tiles.
+// S = 2: the gradient's statistics only; the slice stays small enough for three workgroups per CU.
+enum GradSlot { kLGSum = 0, kLGAbs, kLGSq };
+enum MomentSlot { kLMSum = 0, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr };
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, x);
+  const uint64_t lo = dpp_u32<CTRL>(static_cast<uint32_t>(u)), hi = dpp_u32<CTRL>(static_cast<uint32_t>(u >> 32));
+  return __builtin_bit_cast(double, (hi << 32) | lo);
+}
+
 template <int S>
 struct LaneStats {
-  static constexpr int kSums = S == 1 ? 9 : 3;
-  static constexpr int kMaxes = S == 1 ? 3 : 1;
-  static constexpr int kSlotWords = S == 1 ? 64 : 32;
-  static constexpr int kMaxSlot = kSums;            // + 0 gradient, 1 first moment, 2 second moment
-  static constexpr int kWideSlot = kSums + kMaxes;  // S = 1: two slots, 64 doubles; S = 2: 3 doubles
-  static constexpr int kWords = S == 0 ? 0 : (S == 1 ? (kSums + kMaxes + 2) * 64 : (kSums + kMaxes) * 32 + 8);
+  static constexpr int kGradWords = 3 * 32 + 16;            // three slots of 16 doubles, one of 16 maxima
+  static constexpr int kMomentSums = S == 1 ? 6 : 0;
+  static constexpr int kMomentWords = S == 1 ? (6 + 2) * 64 + 2 * 6 + 4 : 0;  // sums, two maxima, fp64 totals (+ pad)
+  static constexpr int kWords = S == 0 ? 0 : kGradWords + kMomentWords;
   float* acc;      // this wave's slice, null in the plain kernel
   uint32_t tiles;  // tiles since the last widening (uniform)
-  __device__ __forceinline__ int word(int slot, int lane) const {
-    return slot * kSlotWords + (S == 2 ? (lane >> 1) : lane);
+  __device__ __forceinline__ double* grad_sums() const { return reinterpret_cast<double*>(acc); }
+  __device__ __forceinline__ uint32_t* grad_max() const { return reinterpret_cast<uint32_t*>(acc) + 96; }
+  __device__ __forceinline__ float* moment(int slot) const { return acc + kGradWords + slot * 64; }
+  __device__ __forceinline__ double& wide(int lane) const { return reinterpret_cast<double*>(acc + kGradWords + 8 * 64)[lane]; }
+
+  __device__ __forceinline__ void add_grad(int k, int lane, double x) {
+    x += dpp_f64<kDppXor1>(x);
+    x += dpp_f64<kDppXor2>(x);
+    grad_sums()[k * 16 + (lane >> 2)] += x;
   }
-  __device__ __forceinline__ void add(int slot, int lane, float x) {
-    if (S == 2) x += u2f(dpp_u32<kDppXor1>(f2u(x)));
-    acc[word(slot, lane)] += x;
-  }
-  __device__ __forceinline__ void max_bits(int which, int lane, float x) {
+  __device__ __forceinline__ void max_grad(int lane, float x) {
     uint32_t xb = f2u(x);
-    if (S == 2) xb = max(xb, dpp_u32<kDppXor1>(xb));
-    uint32_t* p = reinterpret_cast<uint32_t*>(acc) + word(kMaxSlot + which, lane);
+    xb = max(xb, dpp_u32<kDppXor1>(xb));
+    xb = max(xb, dpp_u32<kDppXor2>(xb));
+    uint32_t* p = grad_max() + (lane >> 2);
     *p = max(*p, xb);
   }
-  // this lane's share of sum k: over the 64 lanes of the wave the shares add up to the wave's sum
-  __device__ __forceinline__ float sum(int k, int lane) const {
-    const float x = acc[word(k, lane)];
-    return (S == 2 && (lane & 1)) ? 0.0f : x;
+  // this lane's share of gradient sum k: over the 64 lanes of the wave the shares add up to the wave's sum
+  __device__ __forceinline__ double grad_share(int k, int lane) const { return (lane & 3) ? 0.0 : grad_sums()[k * 16 + (lane >> 2)]; }
+  __device__ __forceinline__ uint32_t grad_max_share(int lane) const { return grad_max()[lane >> 2]; }
+
+  __device__ __forceinline__ void add(int slot, int lane, float x) { moment(slot)[lane] += x; }
+  // which: 0 first moment, 1 second moment
+  __device__ __forceinline__ void max_bits(int which, int lane, float x) {
+    uint32_t* p = reinterpret_cast<uint32_t*>(moment(6 + which)) + lane;
+    *p = max(*p, f2u(x));
   }
-  __device__ __forceinline__ float lane_max(int which, int lane) const { return acc[word(kMaxSlot + which, lane)]; }
-  // fp64 total of sum `lane` for the current tensor: lanes below kSums only
-  __device__ __forceinline__ double& wide(int lane) {
-    return reinterpret_cast<double*>(acc + kWideSlot * kSlotWords)[lane];
-  }
-  __device__ __forceinline__ void clear_sums(int lane) {
+  __device__ __forceinline__ void clear_moment_sums(int lane) {
 #pragma unroll
-    for (int k = 0; k < kSums; ++k) acc[word(k, lane)] = 0.0f;
+    for (int k = 0; k < kMomentSums; ++k) moment(k)[lane] = 0.0f;
     tiles = 0;
   }
+  __device__ __forceinline__ void clear_grad(int lane) {
+    if (lane < 48) grad_sums()[lane] = 0.0;
+    if (lane < 16) grad_max()[lane] = 0u;
+  }
   __device__ __forceinline__ void clear_all(int lane) {
-    clear_sums(lane);
-#pragma unroll
-    for (int k = 0; k < kMaxes; ++k) acc[word(kMaxSlot + k, lane)] = 0.0f;
-    if (lane < kSums) wide(lane) = 0.0;
+    clear_grad(lane);
+    if (S == 1) {
+      clear_moment_sums(lane);
+      moment(6)[lane] = 0.0f;
+      moment(7)[lane] = 0.0f;
+      if (lane < 6) wide(lane) = 0.0;
+    }
   }
 };
 
@@ -217,90 +237,91 @@ __device__ __forceinline__ double wave_sum(double x) {
   for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
   return x;
 }
-__device__ __forceinline__ float wave_max(float x) {
+__device__ __forceinline__ uint32_t wave_max_bits(uint32_t x) {
 #pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  for (int o = 32; o >= 1; o >>= 1) x = max(x, static_cast<uint32_t>(__shfl_xor(static_cast<int>(x), o, 64)));
   return x;
 }
 
-// fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
+// S = 1: the moments' fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
 template <int S>
 __device__ __forceinline__ void widen_stats(LaneStats<S>& s, int lane) {
+  if (S != 1) return;
 #pragma unroll
-  for (int k = 0; k < LaneStats<S>::kSums; ++k) {
-    const double t = wave_sum(static_cast<double>(s.sum(k, lane)));
+  for (int k = 0; k < LaneStats<S>::kMomentSums; ++k) {
+    const double t = wave_sum(static_cast<double>(s.moment(k)[lane]));
     if (lane == k) s.wide(lane) += t;
   }
-  s.clear_sums(lane);
+  s.clear_moment_sums(lane);
 }
 
+// the wave's statistics -> the tensor's global slots; the slice is cleared
 template <int S>
 __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int lane) {
-  widen_stats(s, lane);
-  float mx[3] = {0.0f, 0.0f, 0.0f};
+  double g[3];
 #pragma unroll
-  for (int k = 0; k < LaneStats<S>::kMaxes; ++k) mx[k] = wave_max(s.lane_max(k, lane));
-  if (lane < LaneStats<S>::kSums) atomicAdd(&slot[lane], s.wide(lane));
-  if (lane == 0) {
-    // non-negative floats order like their bit patterns
-    uint32_t* out = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);
-#pragma unroll
-    for (int k = 0; k < LaneStats<S>::kMaxes; ++k) atomicMax(&out[k], f2u(mx[k]));
+  for (int k = 0; k < 3; ++k) g[k] = wave_sum(s.grad_share(k, lane));
+  const uint32_t gmax = wave_max_bits(s.grad_max_share(lane));
+  uint32_t* out = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);  // max |g|, max |m|, max v: consecutive words
+  if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? g[0] : (lane == 1 ? g[1] : g[2]));
+  if (lane == 3) atomicMax(&out[0], gmax);
+  if (S == 1) {
+    widen_stats(s, lane);
+    const uint32_t mmax = wave_max_bits(f2u(s.moment(6)[lane])), vmax = wave_max_bits(f2u(s.moment(7)[lane]));
+    if (lane < 6) atomicAdd(&slot[kMSum + lane], s.wide(lane));
+    if (lane == 6) atomicMax(&out[1], mmax);
+    if (lane == 7) atomicMax(&out[2], vmax);
   }
   s.clear_all(lane);
 }
 
 // ---- the gradient's statistics under the ticket schedule (S = 2) ----
 // A wave changes tensor with almost every tile there, so it cannot keep sums per tensor.  Instead, after every
-// tile, the wave reduces its four values over its lanes (an fp32 tree), clears its slots and leaves the four
-// values in its record of the current ticket in LDS.  After the ticket's barrier wave 0 adds up the records of
-// the workgroup's waves (fp64) and adds the result to the tensor's global slots: one set of global atomics per
-// workgroup and ticket.  The records belong to the tensor of the ticket's first unit; a wave whose tile lies in
-// another tensor (a ticket that straddles a tensor boundary) adds to that tensor's global slots itself and
-// leaves an empty record.
-struct TicketRecord { float sum[3]; uint32_t max_bits; };
-
-// sum (maximum) of x over lanes 0..31, which hold the lane pairs' words; lanes 32..63 pass zeros
-__device__ __forceinline__ float row_pair_sum(float x) {
-  x += u2f(dpp_u32<kDppXor1>(f2u(x)));
-  x += u2f(dpp_u32<kDppXor2>(f2u(x)));
-  x += u2f(dpp_u32<kDppHalfMirror>(f2u(x)));
-  x += u2f(dpp_u32<kDppMirror>(f2u(x)));
-  return u2f(__builtin_amdgcn_readlane(f2u(x), 0)) + u2f(__builtin_amdgcn_readlane(f2u(x), 16));
-}
-__device__ __forceinline__ uint32_t row_pair_max(uint32_t x) {
-  x = max(x, dpp_u32<kDppXor1>(x));
-  x = max(x, dpp_u32<kDppXor2>(x));
-  x = max(x, dpp_u32<kDppHalfMirror>(x));
-  x = max(x, dpp_u32<kDppMirror>(x));
-  return max(static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 0)), static_cast<uint32_t>(__builtin_amdgcn_readlane(x, 16)));
-}
+// tile, the wave reduces its four values over its lanes, clears its slots and leaves the four values in its
+// record of the current ticket in LDS.  After the ticket's barrier wave 0 adds up the records of the
+// workgroup's waves and adds the result to the tensor's global slots: one set of global atomics per workgroup
+// and ticket.  The records belong to the tensor of the ticket's first unit; a wave whose tile lies in another
+// tensor (a ticket that straddles a tensor boundary) adds to that tensor's global slots itself and leaves an
+// empty record.
+struct TicketRecord { double sum[3]; uint32_t max_bits; uint32_t pad; };
 
 // after a tile: the wave's four values -> its record (or, for a straddling tile, the tensor's global slots)
 __device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketRecord* rec, bool in_wg_tensor, double* slot, int lane) {
-  float t[3];
+  // the slots' 16 words sit in lanes 0..15 (one DPP row); lanes 16..63 pass zeros
+  double t[3];
 #pragma unroll
-  for (int k = 0; k < 3; ++k) t[k] = row_pair_sum(lane < 32 ? s.acc[k * 32 + lane] : 0.0f);
-  uint32_t mx = row_pair_max(lane < 32 ? f2u(s.acc[3 * 32 + lane]) : 0u);
-  if (lane < 32) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) s.acc[k * 32 + lane] = 0.0f;
+  for (int k = 0; k < 3; ++k) {
+    double x = lane < 16 ? s.grad_sums()[k * 16 + lane] : 0.0;
+    x += dpp_f64<kDppXor1>(x);
+    x += dpp_f64<kDppXor2>(x);
+    x += dpp_f64<kDppHalfMirror>(x);
+    x += dpp_f64<kDppMirror>(x);
+    t[k] = x;  // in lanes 0..15
   }
+  uint32_t mx = lane < 16 ? s.grad_max()[lane] : 0u;
+  mx = max(mx, dpp_u32<kDppXor1>(mx));
+  mx = max(mx, dpp_u32<kDppXor2>(mx));
+  mx = max(mx, dpp_u32<kDppHalfMirror>(mx));
+  mx = max(mx, dpp_u32<kDppMirror>(mx));
+  s.clear_grad(lane);
   if (!in_wg_tensor) {
-    if (lane < 3) atomicAdd(&slot[lane], static_cast<double>(lane == 0 ? t[0] : (lane == 1 ? t[1] : t[2])));
+    if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? t[0] : (lane == 1 ? t[1] : t[2]));
     if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
-    t[0] = t[1] = t[2] = 0.0f;
+    t[0] = t[1] = t[2] = 0.0;
     mx = 0u;
   }
-  if (lane == 0) *reinterpret_cast<float4*>(rec) = make_float4(t[0], t[1], t[2], u2f(mx));
+  if (lane == 0) {
+    rec->sum[0] = t[0]; rec->sum[1] = t[1]; rec->sum[2] = t[2];
+    rec->max_bits = mx;
+  }
 }
 
 // wave 0, after the ticket's barrier: the records of the workgroup's waves -> the tensor's global slots
 __device__ __forceinline__ void ticket_stats_flush(const TicketRecord* recs, double* slot, int lane) {
   static_assert(kWavesPerGroup == 8, "one record per lane of the first eight");
-  const float4 r = *reinterpret_cast<const float4*>(recs + (lane & 7));
-  double t0 = r.x, t1 = r.y, t2 = r.z;
-  uint32_t mx = f2u(r.w);
+  const TicketRecord& r = recs[lane & 7];
+  double t0 = r.sum[0], t1 = r.sum[1], t2 = r.sum[2];
+  uint32_t mx = r.max_bits;
 #pragma unroll
   for (int o = 1; o <= 4; o <<= 1) {
     t0 += __shfl_xor(t0, o, 64);
@@ -308,7 +329,7 @@ __device__ __forceinline__ void ticket_stats_flush(const TicketRecord* recs, dou
     t2 += __shfl_xor(t2, o, 64);
     mx = max(mx, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx), o, 64)));
   }
-  if (lane < 3) atomicAdd(&slot[lane], lane == 0 ? t0 : (lane == 1 ? t1 : t2));
+  if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? t0 : (lane == 1 ? t1 : t2));
   if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
 }
 
@@ -536,18 +557,20 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
   }
 
   if (STATS) {
-    float sg_sum = 0.0f, sg_abs = 0.0f, sg_sq = 0.0f, sg_max = 0.0f;
+    double sg_sum = 0.0, sg_abs = 0.0, sg_sq = 0.0;  // fp64 from the first addition (pads are zeros)
+    float sg_max = 0.0f;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      sg_sum += g[n];
-      sg_abs += fabsf(g[n]);
-      sg_sq = __builtin_fmaf(g[n], g[n], sg_sq);
+      const double gd = static_cast<double>(g[n]);
+      sg_sum += gd;
+      sg_abs += __builtin_fabs(gd);
+      sg_sq = __builtin_fma(gd, gd, sg_sq);
       sg_max = fmaxf(sg_max, fabsf(g[n]));
     }
-    st.add(kLGSum, lane, sg_sum);
-    st.add(kLGAbs, lane, sg_abs);
-    st.add(kLGSq, lane, sg_sq);
-    st.max_bits(0, lane, sg_max);
+    st.add_grad(kLGSum, lane, sg_sum);
+    st.add_grad(kLGAbs, lane, sg_abs);
+    st.add_grad(kLGSq, lane, sg_sq);
+    st.max_grad(lane, sg_max);
   }
 
   // ---- moments: m_t = beta1*m_{t-1} + (1-beta1)*g ; v_t = beta2*v_{t-1} + (1-beta2)*g^2 ----
@@ -631,7 +654,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     r = u2f(rb);
   }
   if (STATS == 1) {
-    st.max_bits(vL < 2 ? 1 : 2, lane, r);
+    st.max_bits(vL < 2 ? 0 : 1, lane, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
@@ -886,7 +909,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + kWavesPerGroup * LaneStats<STATS>::kWords];
   __shared__ uint32_t drawn[2];  // the ticket being worked on and the next one, alternating
   // gradient statistics of the two tickets in flight, one record per wave (STATS 2 with tickets)
-  __shared__ __attribute__((aligned(16))) TicketRecord ticket_rec[2][kWavesPerGroup];
+  __shared__ TicketRecord ticket_rec[2][kWavesPerGroup];
   const bool tickets = a.sched != nullptr;
   if (threadIdx.x == 0) drawn[0] = blockIdx.x;
   // the value tables of every width (4 KB), the search table of the second-moment widths this launch can write
@@ -982,7 +1005,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
     if (tickets) {
       if constexpr (STATS == 2) {
         // a wave without a unit in this ticket (the launch's last one) leaves an empty record
-        if (c_begin >= c_end && lane == 0) *reinterpret_cast<float4*>(&ticket_rec[turn][wave]) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (c_begin >= c_end && lane < 4) reinterpret_cast<double*>(&ticket_rec[turn][wave])[lane] = 0.0;
       }
       if (threadIdx.x == 0) drawn[turn ^ 1u] = next_ticket;
       __syncthreads();  // the workgroup goes on together

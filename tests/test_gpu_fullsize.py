@@ -141,9 +141,9 @@ def test_full_size_sampled_parity(oracle, name):
             for l in range(0, L, max(1, L // 24)):
                 g64 = dm.grad[l].double()
                 assert gs[l].count == g64.numel()
-                assert abs(gs[l].g_sq_sum - float((g64 * g64).sum())) <= 1e-5 * float((g64 * g64).sum())
-                assert abs(gs[l].g_abs_sum - float(g64.abs().sum())) <= 1e-5 * float(g64.abs().sum())
-                assert abs(gs[l].g_sum - float(g64.sum())) <= 1e-5 * float(g64.abs().sum())
+                assert abs(gs[l].g_sq_sum - float((g64 * g64).sum())) <= 1e-11 * float((g64 * g64).sum())
+                assert abs(gs[l].g_abs_sum - float(g64.abs().sum())) <= 1e-11 * float(g64.abs().sum())
+                assert abs(gs[l].g_sum - float(g64.sum())) <= 1e-11 * float(g64.abs().sum())
                 assert gs[l].g_absmax == float(g64.abs().max())
                 # the stored scales are the block maxima, so the maxima of the moments are the largest scales
                 assert gs[l].m_absmax == float(dm.m_scales[l].max())
@@ -295,7 +295,7 @@ def test_tensor_beyond_2_31_elements(oracle):
     gs = ctx.stats(2, dm.stream)
     assert gs[1].count == n_big and gs[0].count == 70_001
     g64 = dm.grad[1].double()
-    assert abs(gs[1].g_sq_sum - float((g64 * g64).sum())) <= 1e-5 * float((g64 * g64).sum())
+    assert abs(gs[1].g_sq_sum - float((g64 * g64).sum())) <= 1e-11 * float((g64 * g64).sum())
     assert gs[1].g_absmax == float(g64.abs().max())
     del g64
     ctx.close()
@@ -377,10 +377,10 @@ def test_device_resident_loop_at_full_size(oracle, alg1):
                 s.count, s.g_sum, s.g_abs_sum, s.g_sq_sum = g64.numel(), float(g64.sum()), float(g64.abs().sum()), float((g64 * g64).sum())
                 stats.append(s)
             bm_o, bv_o, sc = oracle.decide(ema, stats, t, **kw)
-            assert np.allclose(after["score"], sc, rtol=0, atol=1e-5), f"step {t} scores"
-            assert np.allclose(after["ema"], (ema.n_ema, ema.r_ema, ema.v_ema), rtol=1e-6, atol=0), f"step {t} EMAs"
+            assert np.allclose(after["score"], sc, rtol=0, atol=1e-8), f"step {t} scores"
+            assert np.allclose(after["ema"], (ema.n_ema, ema.r_ema, ema.v_ema), rtol=1e-10, atol=0), f"step {t} EMAs"
             for l in range(L):
-                near = any(abs(sc[l] - x) < 1e-4 or abs(sc[l] - 0.5 - x) < 1e-4 for x in thr)
+                near = any(abs(sc[l] - x) < 1e-7 or abs(sc[l] - 0.5 - x) < 1e-7 for x in thr)
                 if not near:   # by-product order: the widths the next step writes; written order: this step's
                     assert after["next"][l] == (int(bm_o[l]), int(bv_o[l])), f"step {t} tensor {l}: score {sc[l]}"
             changed += sum(a != b for a, b in zip(after["next"], info["stored"]))
