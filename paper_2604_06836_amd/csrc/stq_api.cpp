@@ -293,7 +293,7 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   const bool want_stats = stats != 0;
   // the plain kernel and the gradient-statistics one fit six waves per SIMD (three workgroups per CU),
   // the full statistics variant and the wide-state one two workgroups
-  const uint32_t cap_cu = (stats == 1 || mode == 2) ? 2 : 8;
+    const uint32_t cap_cu = (stats == 1 || mode == 2) ? 2 : 8;
   const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
   const uint32_t wpg = kWavesPerGroup;
   const uint32_t max_groups = ctx->n_cu * per_cu;

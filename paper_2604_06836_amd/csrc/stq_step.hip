@@ -157,15 +157,20 @@ constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16 
 // (The sums of squares use fused multiply-adds: the fixed operation order binds the Adam
 // arithmetic, not the statistics, which are compared within a tolerance.)
 // Running statistics of one wave, kept in its LDS slice so that they cost no registers between the places
-// that add to them.
+// that add to them.  A contribution is first combined over a few neighbouring lanes with DPP steps, then one
+// lane of the group adds it to the group's word with an LDS atomic that returns nothing: the wave does not
+// wait for it, where a read-modify-write would put an LDS round trip into every quarter's dependency chain
+// (that latency, not the arithmetic, was most of the statistics' cost: it showed when fewer waves were
+// resident to hide it).  The atomics are issued from 8 or 16 lanes: from all 64 they are several times slower.
 //  * The gradient's three sums (all that the bit-width decision reads, Eq. 2, 3, 8) are taken in fp64 from the
 //    first addition on: fp64 vector additions issue at the rate of fp32 ones here, and a decision that compares a
 //    score with a threshold should not hinge on the rounding of a sum (the variance in Eq. 3 is a difference of
-//    two such sums).  Groups of four neighbouring lanes combine their contributions with two DPP steps and share
-//    one fp64 word of a 16-word slot -- all four write the same value to it; the gradient's maximum likewise in
-//    a 16-word slot of bit patterns (all maxima are non-negative, so they order like their bit patterns).
-//  * S = 1 adds the moments' six fp32 sums and two maxima, one word per lane and slot; their sums since the last
-//    widening are added to fp64 totals (lane k < 6 of the last slot) every kStatFlushTiles tiles.
+//    two such sums).  Groups of four lanes, 16-word slots; the gradient's maximum likewise in a 16-word slot of
+//    bit patterns (all maxima are non-negative, so they order like their bit patterns).
+//  * S = 1 adds the moments' six fp32 sums (groups of eight lanes, 8-word slots) and two maxima (the owner lanes
+//    of the block scales hold them: lanes 0..31 the first moment's, 32..63 the second's, so a group of four is
+//    of one kind); the sums since the last widening are added to fp64 totals (lane k < 6 of the last slot)
+//    every kStatFlushTiles tiles.
 // S = 2: the gradient's statistics only; the slice stays small enough for three workgroups per CU.
 enum GradSlot { kLGSum = 0, kLGAbs, kLGSq };
 enum MomentSlot { kLMSum = 0, kLMSq, kLMErr, kLVSum, kLVSq, kLVErr };
@@ -181,40 +186,49 @@ template <int S>
 struct LaneStats {
   static constexpr int kGradWords = 3 * 32 + 16;            // three slots of 16 doubles, one of 16 maxima
   static constexpr int kMomentSums = S == 1 ? 6 : 0;
-  static constexpr int kMomentWords = S == 1 ? (6 + 2) * 64 + 2 * 6 + 4 : 0;  // sums, two maxima, fp64 totals (+ pad)
+  static constexpr int kMomentWords = S == 1 ? 6 * 8 + 2 * 16 + 2 * 6 + 4 : 0;  // sums, two maxima, fp64 totals (+ pad)
   static constexpr int kWords = S == 0 ? 0 : kGradWords + kMomentWords;
   float* acc;      // this wave's slice, null in the plain kernel
   uint32_t tiles;  // tiles since the last widening (uniform)
   __device__ __forceinline__ double* grad_sums() const { return reinterpret_cast<double*>(acc); }
   __device__ __forceinline__ uint32_t* grad_max() const { return reinterpret_cast<uint32_t*>(acc) + 96; }
-  __device__ __forceinline__ float* moment(int slot) const { return acc + kGradWords + slot * 64; }
-  __device__ __forceinline__ double& wide(int lane) const { return reinterpret_cast<double*>(acc + kGradWords + 8 * 64)[lane]; }
+  __device__ __forceinline__ float* moment(int slot) const { return acc + kGradWords + slot * 8; }  // sums: 8 words each
+  __device__ __forceinline__ uint32_t* moment_max() const { return reinterpret_cast<uint32_t*>(acc + kGradWords + 6 * 8); }  // 2 x 16 words
+  __device__ __forceinline__ double& wide(int lane) const { return reinterpret_cast<double*>(acc + kGradWords + 6 * 8 + 2 * 16)[lane]; }
 
   __device__ __forceinline__ void add_grad(int k, int lane, double x) {
     x += dpp_f64<kDppXor1>(x);
     x += dpp_f64<kDppXor2>(x);
-    grad_sums()[k * 16 + (lane >> 2)] += x;
+    if ((lane & 3) == 0)
+      __hip_atomic_fetch_add(&grad_sums()[k * 16 + (lane >> 2)], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
   __device__ __forceinline__ void max_grad(int lane, float x) {
     uint32_t xb = f2u(x);
     xb = max(xb, dpp_u32<kDppXor1>(xb));
     xb = max(xb, dpp_u32<kDppXor2>(xb));
-    uint32_t* p = grad_max() + (lane >> 2);
-    *p = max(*p, xb);
+    if ((lane & 3) == 0)
+      __hip_atomic_fetch_max(grad_max() + (lane >> 2), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
   // this lane's share of gradient sum k: over the 64 lanes of the wave the shares add up to the wave's sum
   __device__ __forceinline__ double grad_share(int k, int lane) const { return (lane & 3) ? 0.0 : grad_sums()[k * 16 + (lane >> 2)]; }
   __device__ __forceinline__ uint32_t grad_max_share(int lane) const { return grad_max()[lane >> 2]; }
 
-  __device__ __forceinline__ void add(int slot, int lane, float x) { moment(slot)[lane] += x; }
+  __device__ __forceinline__ void add(int slot, int lane, float x) {
+    x += u2f(dpp_u32<kDppXor1>(f2u(x)));
+    x += u2f(dpp_u32<kDppXor2>(f2u(x)));
+    x += u2f(dpp_u32<kDppHalfMirror>(f2u(x)));
+    if ((lane & 7) == 0) __hip_atomic_fetch_add(&moment(slot)[lane >> 3], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+  }
   // which: 0 first moment, 1 second moment
   __device__ __forceinline__ void max_bits(int which, int lane, float x) {
-    uint32_t* p = reinterpret_cast<uint32_t*>(moment(6 + which)) + lane;
-    *p = max(*p, f2u(x));
+    uint32_t xb = f2u(x);
+    xb = max(xb, dpp_u32<kDppXor1>(xb));
+    xb = max(xb, dpp_u32<kDppXor2>(xb));
+    if ((lane & 3) == 0)
+      __hip_atomic_fetch_max(moment_max() + which * 16 + (lane >> 2), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
   __device__ __forceinline__ void clear_moment_sums(int lane) {
-#pragma unroll
-    for (int k = 0; k < kMomentSums; ++k) moment(k)[lane] = 0.0f;
+    if (S == 1 && lane < 48) moment(0)[lane] = 0.0f;  // six slots of 8 words
     tiles = 0;
   }
   __device__ __forceinline__ void clear_grad(int lane) {
@@ -225,8 +239,7 @@ struct LaneStats {
     clear_grad(lane);
     if (S == 1) {
       clear_moment_sums(lane);
-      moment(6)[lane] = 0.0f;
-      moment(7)[lane] = 0.0f;
+      if (lane < 32) moment_max()[lane] = 0u;
       if (lane < 6) wide(lane) = 0.0;
     }
   }
@@ -247,9 +260,10 @@ __device__ __forceinline__ uint32_t wave_max_bits(uint32_t x) {
 template <int S>
 __device__ __forceinline__ void widen_stats(LaneStats<S>& s, int lane) {
   if (S != 1) return;
+  wave_lds_sync();  // the atomics of every lane before the reads below
 #pragma unroll
   for (int k = 0; k < LaneStats<S>::kMomentSums; ++k) {
-    const double t = wave_sum(static_cast<double>(s.moment(k)[lane]));
+    const double t = wave_sum(lane < 8 ? static_cast<double>(s.moment(k)[lane]) : 0.0);
     if (lane == k) s.wide(lane) += t;
   }
   s.clear_moment_sums(lane);
@@ -259,6 +273,7 @@ __device__ __forceinline__ void widen_stats(LaneStats<S>& s, int lane) {
 template <int S>
 __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int lane) {
   double g[3];
+  wave_lds_sync();  // the atomics of every lane before the reads below
 #pragma unroll
   for (int k = 0; k < 3; ++k) g[k] = wave_sum(s.grad_share(k, lane));
   const uint32_t gmax = wave_max_bits(s.grad_max_share(lane));
@@ -267,7 +282,7 @@ __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int l
   if (lane == 3) atomicMax(&out[0], gmax);
   if (S == 1) {
     widen_stats(s, lane);
-    const uint32_t mmax = wave_max_bits(f2u(s.moment(6)[lane])), vmax = wave_max_bits(f2u(s.moment(7)[lane]));
+    const uint32_t mmax = wave_max_bits(s.moment_max()[lane & 15]), vmax = wave_max_bits(s.moment_max()[16 + (lane & 15)]);
     if (lane < 6) atomicAdd(&slot[kMSum + lane], s.wide(lane));
     if (lane == 6) atomicMax(&out[1], mmax);
     if (lane == 7) atomicMax(&out[2], vmax);
@@ -289,6 +304,7 @@ struct TicketRecord { double sum[3]; uint32_t max_bits; uint32_t pad; };
 __device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketRecord* rec, bool in_wg_tensor, double* slot, int lane) {
   // the slots' 16 words sit in lanes 0..15 (one DPP row); lanes 16..63 pass zeros
   double t[3];
+  wave_lds_sync();  // the atomics of every lane before the reads below
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
     double x = lane < 16 ? s.grad_sums()[k * 16 + lane] : 0.0;
