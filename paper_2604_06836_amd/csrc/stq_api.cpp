@@ -291,9 +291,8 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   // statistics: all of them, or only the gradient's (the flag for all wins)
   const int stats = (hp->flags & STQ_FLAG_STATS) ? 1 : ((hp->flags & STQ_FLAG_STATS_GRAD) ? 2 : 0);
   const bool want_stats = stats != 0;
-  // the plain kernel and the gradient-statistics one fit six waves per SIMD (three workgroups per CU),
-  // the full statistics variant and the wide-state one two workgroups
-    const uint32_t cap_cu = (stats == 1 || mode == 2) ? 2 : 8;
+  // every variant fits six waves per SIMD (three workgroups per CU) except the wide-state one (two)
+  const uint32_t cap_cu = mode == 2 ? 2 : 8;
   const uint32_t per_cu = ctx->groups_per_cu < cap_cu ? ctx->groups_per_cu : cap_cu;
   const uint32_t wpg = kWavesPerGroup;
   const uint32_t max_groups = ctx->n_cu * per_cu;
@@ -313,12 +312,11 @@ int launch_table(stq_ctx* ctx, const TensorDesc* d_desc, uint32_t n, uint32_t to
   else if (stats == 2) a.chunk = static_cast<uint32_t>(per_wave >= 64 ? 4 : per_wave);  // its flush is cheap
   else a.chunk = per_wave >= 64 ? 4 : 1;
   if (ctx->chunk_override && !want_stats) a.chunk = ctx->chunk_override;
-  // tickets (see step_kernel) for large launches, unless every statistic is collected (that variant keeps one
-  // contiguous range per wave)
-  a.sched = (stats == 1 || units < ctx->ticket_min_units) ? nullptr : (sched ? sched : ctx->d_sched);
+  // tickets (see step_kernel) for large launches
+  a.sched = units < ctx->ticket_min_units ? nullptr : (sched ? sched : ctx->d_sched);
 #ifdef STQ_TUNING_ENV
   if (std::getenv("STQ_NO_TICKETS")) a.sched = nullptr;
-  if (std::getenv("STQ_TICKETS") && stats != 1) a.sched = sched ? sched : ctx->d_sched;
+  if (std::getenv("STQ_TICKETS")) a.sched = sched ? sched : ctx->d_sched;
 #endif
   return launch_step(a, hp->grad_dtype == 1, stats, mode, groups, stream) == 0 ? STQ_OK : STQ_EHIP;
 }

@@ -181,172 +181,210 @@ __device__ __forceinline__ double dpp_f64(double x) {
   const uint64_t lo = dpp_u32<CTRL>(static_cast<uint32_t>(u)), hi = dpp_u32<CTRL>(static_cast<uint32_t>(u >> 32));
   return __builtin_bit_cast(double, (hi << 32) | lo);
 }
+// Sums and maxima over groups of 4, 8 or 16 neighbouring lanes, left in every lane of the group.  DPP steps
+// only: a shuffle through LDS needs a lane-dependent address register, and the compiler keeps those
+// alive across the whole tile loop.
+__device__ __forceinline__ double quad_sum(double x) {
+  x += dpp_f64<kDppXor1>(x);
+  x += dpp_f64<kDppXor2>(x);
+  return x;
+}
+__device__ __forceinline__ double octet_sum(double x) {
+  x = quad_sum(x);
+  x += dpp_f64<kDppHalfMirror>(x);
+  return x;
+}
+__device__ __forceinline__ double row_sum(double x) {
+  x = octet_sum(x);
+  x += dpp_f64<kDppMirror>(x);
+  return x;
+}
+__device__ __forceinline__ float octet_sum(float x) {
+  x += u2f(dpp_u32<kDppXor1>(f2u(x)));
+  x += u2f(dpp_u32<kDppXor2>(f2u(x)));
+  x += u2f(dpp_u32<kDppHalfMirror>(f2u(x)));
+  return x;
+}
+__device__ __forceinline__ uint32_t quad_max(uint32_t x) {
+  x = max(x, dpp_u32<kDppXor1>(x));
+  x = max(x, dpp_u32<kDppXor2>(x));
+  return x;
+}
+__device__ __forceinline__ uint32_t octet_max(uint32_t x) {
+  x = quad_max(x);
+  return max(x, dpp_u32<kDppHalfMirror>(x));
+}
+__device__ __forceinline__ uint32_t row_max(uint32_t x) {
+  x = octet_max(x);
+  return max(x, dpp_u32<kDppMirror>(x));
+}
 
+// Layout of a wave's slice (32-bit words), S = 2 | S = 1:
+//   gradient sums  3 slots of G doubles, G = 16 | 8 (one word per group of 64/G lanes)
+//   maxima         16 | 32 words: [0, G) max|g|; S = 1: [16, 24) max|m| (lanes 0..31 own the first moment's
+//                  block scales), [24, 32) max v (lanes 32..63); words [8, 16) stay 0
+//   S = 1 only     moment sums: 6 slots of 8 floats; fp64 totals of the six since the last flush (+ pad)
+// S = 1 takes the smaller gradient slots so that three workgroups still fit a CU's LDS.
 template <int S>
 struct LaneStats {
-  static constexpr int kGradWords = 3 * 32 + 16;            // three slots of 16 doubles, one of 16 maxima
+  static constexpr int kGShift = S == 1 ? 3 : 2;  // log2 of the lanes that share a gradient word
+  static constexpr int kG = 64 >> kGShift;        // words per gradient slot
+  static constexpr int kMaxWords = S == 1 ? 32 : 16;
   static constexpr int kMomentSums = S == 1 ? 6 : 0;
-  static constexpr int kMomentWords = S == 1 ? 6 * 8 + 2 * 16 + 2 * 6 + 4 : 0;  // sums, two maxima, fp64 totals (+ pad)
-  static constexpr int kWords = S == 0 ? 0 : kGradWords + kMomentWords;
+  static constexpr int kMaxOff = 3 * 2 * kG, kMomentOff = kMaxOff + kMaxWords, kWideOff = kMomentOff + 6 * 8;
+  static constexpr int kWords = S == 0 ? 0 : (S == 1 ? kWideOff + 2 * 6 + 4 : kMomentOff);
   float* acc;      // this wave's slice, null in the plain kernel
-  uint32_t tiles;  // tiles since the last widening (uniform)
+  uint32_t tiles;  // tiles since the last widening (uniform; stripes only)
   __device__ __forceinline__ double* grad_sums() const { return reinterpret_cast<double*>(acc); }
-  __device__ __forceinline__ uint32_t* grad_max() const { return reinterpret_cast<uint32_t*>(acc) + 96; }
-  __device__ __forceinline__ float* moment(int slot) const { return acc + kGradWords + slot * 8; }  // sums: 8 words each
-  __device__ __forceinline__ uint32_t* moment_max() const { return reinterpret_cast<uint32_t*>(acc + kGradWords + 6 * 8); }  // 2 x 16 words
-  __device__ __forceinline__ double& wide(int lane) const { return reinterpret_cast<double*>(acc + kGradWords + 6 * 8 + 2 * 16)[lane]; }
+  __device__ __forceinline__ uint32_t* maxima() const { return reinterpret_cast<uint32_t*>(acc) + kMaxOff; }
+  __device__ __forceinline__ float* moment_sums() const { return acc + kMomentOff; }
+  __device__ __forceinline__ double& wide(int k) const { return reinterpret_cast<double*>(acc + kWideOff)[k]; }
 
   __device__ __forceinline__ void add_grad(int k, int lane, double x) {
-    x += dpp_f64<kDppXor1>(x);
-    x += dpp_f64<kDppXor2>(x);
-    if ((lane & 3) == 0)
-      __hip_atomic_fetch_add(&grad_sums()[k * 16 + (lane >> 2)], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    x = S == 1 ? octet_sum(x) : quad_sum(x);
+    if ((lane & ((1 << kGShift) - 1)) == 0)
+      __hip_atomic_fetch_add(&grad_sums()[k * kG + (lane >> kGShift)], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
   __device__ __forceinline__ void max_grad(int lane, float x) {
-    uint32_t xb = f2u(x);
-    xb = max(xb, dpp_u32<kDppXor1>(xb));
-    xb = max(xb, dpp_u32<kDppXor2>(xb));
-    if ((lane & 3) == 0)
-      __hip_atomic_fetch_max(grad_max() + (lane >> 2), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    const uint32_t xb = S == 1 ? octet_max(f2u(x)) : quad_max(f2u(x));
+    if ((lane & ((1 << kGShift) - 1)) == 0)
+      __hip_atomic_fetch_max(maxima() + (lane >> kGShift), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
-  // this lane's share of gradient sum k: over the 64 lanes of the wave the shares add up to the wave's sum
-  __device__ __forceinline__ double grad_share(int k, int lane) const { return (lane & 3) ? 0.0 : grad_sums()[k * 16 + (lane >> 2)]; }
-  __device__ __forceinline__ uint32_t grad_max_share(int lane) const { return grad_max()[lane >> 2]; }
-
   __device__ __forceinline__ void add(int slot, int lane, float x) {
-    x += u2f(dpp_u32<kDppXor1>(f2u(x)));
-    x += u2f(dpp_u32<kDppXor2>(f2u(x)));
-    x += u2f(dpp_u32<kDppHalfMirror>(f2u(x)));
-    if ((lane & 7) == 0) __hip_atomic_fetch_add(&moment(slot)[lane >> 3], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    x = octet_sum(x);
+    if ((lane & 7) == 0)
+      __hip_atomic_fetch_add(&moment_sums()[slot * 8 + (lane >> 3)], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
-  // which: 0 first moment, 1 second moment
-  __device__ __forceinline__ void max_bits(int which, int lane, float x) {
-    uint32_t xb = f2u(x);
-    xb = max(xb, dpp_u32<kDppXor1>(xb));
-    xb = max(xb, dpp_u32<kDppXor2>(xb));
+  // the maximum of a block of a moment, from its owner lanes (a quad is of one kind: see the layout)
+  __device__ __forceinline__ void max_moment(int lane, float x) {
+    const uint32_t xb = quad_max(f2u(x));
     if ((lane & 3) == 0)
-      __hip_atomic_fetch_max(moment_max() + which * 16 + (lane >> 2), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      __hip_atomic_fetch_max(maxima() + 16 + (lane >> 2), xb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   }
   __device__ __forceinline__ void clear_moment_sums(int lane) {
-    if (S == 1 && lane < 48) moment(0)[lane] = 0.0f;  // six slots of 8 words
+    if (S == 1 && lane < 48) moment_sums()[lane] = 0.0f;
     tiles = 0;
   }
   __device__ __forceinline__ void clear_grad(int lane) {
-    if (lane < 48) grad_sums()[lane] = 0.0;
-    if (lane < 16) grad_max()[lane] = 0u;
+    if (lane < 3 * kG) grad_sums()[lane] = 0.0;
+    if (lane < kMaxWords) maxima()[lane] = 0u;
   }
   __device__ __forceinline__ void clear_all(int lane) {
     clear_grad(lane);
     if (S == 1) {
       clear_moment_sums(lane);
-      if (lane < 32) moment_max()[lane] = 0u;
       if (lane < 6) wide(lane) = 0.0;
     }
   }
+  // The reductions of a slice, for the flushes below (call wave_lds_sync() first).
+  // Gradient sum k (0..2), complete, in the lanes [k*kG, (k+1)*kG); zero in the lanes from 3*kG on.
+  __device__ __forceinline__ double reduced_grad(int lane) const {
+    const double x = lane < 3 * kG ? grad_sums()[lane] : 0.0;
+    return S == 1 ? octet_sum(x) : row_sum(x);
+  }
+  // Moment sum k (0..5) since the last clearing, in the lanes [8k, 8k+8); zero from lane 48 on.
+  __device__ __forceinline__ double reduced_moment(int lane) const {
+    return octet_sum(lane < 48 ? static_cast<double>(moment_sums()[lane]) : 0.0);
+  }
+  // max|g| in lane 0; S = 1: max|m| in lane 16, max v in lane 24.
+  __device__ __forceinline__ uint32_t reduced_max(int lane) const {
+    const uint32_t x = lane < kMaxWords ? maxima()[lane] : 0u;
+    return S == 1 ? octet_max(x) : row_max(x);
+  }
+  // lane holds gradient sum `k` / moment sum `k` / maximum `k` (0 g, 1 m, 2 v) of the reductions above
+  __device__ __forceinline__ static bool grad_lead(int lane, int& k) { k = lane >> (6 - kGShift); return lane < 3 * kG && (lane & (kG - 1)) == 0; }
+  __device__ __forceinline__ static bool moment_lead(int lane, int& k) { k = lane >> 3; return S == 1 && lane < 48 && (lane & 7) == 0; }
+  __device__ __forceinline__ static bool max_lead(int lane, int& k) {
+    k = lane == 0 ? 0 : (lane == 16 ? 1 : 2);
+    return lane == 0 || (S == 1 && (lane == 16 || lane == 24));
+  }
 };
 
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-  return x;
-}
-__device__ __forceinline__ uint32_t wave_max_bits(uint32_t x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = max(x, static_cast<uint32_t>(__shfl_xor(static_cast<int>(x), o, 64)));
-  return x;
-}
-
-// S = 1: the moments' fp32 lane sums -> fp64 wave totals, kept in lane k of `wide`
+// S = 1: the moments' fp32 sums -> the wave's fp64 totals
 template <int S>
 __device__ __forceinline__ void widen_stats(LaneStats<S>& s, int lane) {
   if (S != 1) return;
-  wave_lds_sync();  // the atomics of every lane before the reads below
-#pragma unroll
-  for (int k = 0; k < LaneStats<S>::kMomentSums; ++k) {
-    const double t = wave_sum(lane < 8 ? static_cast<double>(s.moment(k)[lane]) : 0.0);
-    if (lane == k) s.wide(lane) += t;
-  }
+  asm volatile("" : "+v"(lane));  // nothing derived from the lane index is worth keeping across the tile loop
+  wave_lds_sync();                // the atomics of every lane before the reads below
+  const double t = s.reduced_moment(lane);
+  int k;
+  if (LaneStats<S>::moment_lead(lane, k)) s.wide(k) += t;
   s.clear_moment_sums(lane);
 }
 
-// the wave's statistics -> the tensor's global slots; the slice is cleared
+// the wave's statistics -> the tensor's global slots; the slice is cleared  (stripes)
 template <int S>
 __device__ __forceinline__ void flush_stats(LaneStats<S>& s, double* slot, int lane) {
-  double g[3];
-  wave_lds_sync();  // the atomics of every lane before the reads below
-#pragma unroll
-  for (int k = 0; k < 3; ++k) g[k] = wave_sum(s.grad_share(k, lane));
-  const uint32_t gmax = wave_max_bits(s.grad_max_share(lane));
+  asm volatile("" : "+v"(lane));
+  wave_lds_sync();
+  const double g = s.reduced_grad(lane);
+  const uint32_t mx = s.reduced_max(lane);
   uint32_t* out = reinterpret_cast<uint32_t*>(&slot[kMaxGM]);  // max |g|, max |m|, max v: consecutive words
-  if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? g[0] : (lane == 1 ? g[1] : g[2]));
-  if (lane == 3) atomicMax(&out[0], gmax);
+  int k;
+  if (LaneStats<S>::grad_lead(lane, k)) atomicAdd(&slot[kGSum + k], g);
+  if (LaneStats<S>::max_lead(lane, k)) atomicMax(&out[k], mx);
   if (S == 1) {
     widen_stats(s, lane);
-    const uint32_t mmax = wave_max_bits(s.moment_max()[lane & 15]), vmax = wave_max_bits(s.moment_max()[16 + (lane & 15)]);
+    wave_lds_sync();
     if (lane < 6) atomicAdd(&slot[kMSum + lane], s.wide(lane));
-    if (lane == 6) atomicMax(&out[1], mmax);
-    if (lane == 7) atomicMax(&out[2], vmax);
   }
   s.clear_all(lane);
 }
 
-// ---- the gradient's statistics under the ticket schedule (S = 2) ----
+// ---- statistics under the ticket schedule ----
 // A wave changes tensor with almost every tile there, so it cannot keep sums per tensor.  Instead, after every
-// tile, the wave reduces its four values over its lanes, clears its slots and leaves the four values in its
-// record of the current ticket in LDS.  After the ticket's barrier wave 0 adds up the records of the
-// workgroup's waves and adds the result to the tensor's global slots: one set of global atomics per workgroup
-// and ticket.  The records belong to the tensor of the ticket's first unit; a wave whose tile lies in another
-// tensor (a ticket that straddles a tensor boundary) adds to that tensor's global slots itself and leaves an
-// empty record.
-struct TicketRecord { double sum[3]; uint32_t max_bits; uint32_t pad; };
+// tile, the wave reduces its values over its lanes, clears its slice and leaves the values in its record of
+// the current ticket in LDS.  After the ticket's barrier wave 0 adds up the records of the workgroup's waves
+// and adds the result to the tensor's global slots: one set of global atomics per workgroup and ticket.  The
+// records belong to the tensor of the ticket's first unit; a wave whose tile lies in another tensor (a ticket
+// that straddles a tensor boundary) adds to that tensor's global slots itself and leaves an empty record.
+template <int S>
+struct TicketRecord {
+  double sum[S == 1 ? 9 : 3];           // in the order of the global slots from kGSum on
+  uint32_t max_bits[S == 1 ? 4 : 2];    // max|g|, (max|m|, max v,) pad
+};
 
-// after a tile: the wave's four values -> its record (or, for a straddling tile, the tensor's global slots)
-__device__ __forceinline__ void ticket_stats_tile(LaneStats<2>& s, TicketRecord* rec, bool in_wg_tensor, double* slot, int lane) {
-  // the slots' 16 words sit in lanes 0..15 (one DPP row); lanes 16..63 pass zeros
-  double t[3];
-  wave_lds_sync();  // the atomics of every lane before the reads below
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    double x = lane < 16 ? s.grad_sums()[k * 16 + lane] : 0.0;
-    x += dpp_f64<kDppXor1>(x);
-    x += dpp_f64<kDppXor2>(x);
-    x += dpp_f64<kDppHalfMirror>(x);
-    x += dpp_f64<kDppMirror>(x);
-    t[k] = x;  // in lanes 0..15
-  }
-  uint32_t mx = lane < 16 ? s.grad_max()[lane] : 0u;
-  mx = max(mx, dpp_u32<kDppXor1>(mx));
-  mx = max(mx, dpp_u32<kDppXor2>(mx));
-  mx = max(mx, dpp_u32<kDppHalfMirror>(mx));
-  mx = max(mx, dpp_u32<kDppMirror>(mx));
+// after a tile: the wave's values -> its record (or, for a straddling tile, the tensor's global slots)
+template <int S>
+__device__ __forceinline__ void ticket_stats_tile(LaneStats<S>& s, TicketRecord<S>* rec, bool in_wg_tensor, double* slot, int lane) {
+  asm volatile("" : "+v"(lane));
+  wave_lds_sync();
+  double g = s.reduced_grad(lane);
+  double mo = S == 1 ? s.reduced_moment(lane) : 0.0;
+  uint32_t mx = s.reduced_max(lane);
   s.clear_grad(lane);
+  s.clear_moment_sums(lane);
+  int kg, km, kx;
+  const bool lg = LaneStats<S>::grad_lead(lane, kg), lm = LaneStats<S>::moment_lead(lane, km), lx = LaneStats<S>::max_lead(lane, kx);
   if (!in_wg_tensor) {
-    if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? t[0] : (lane == 1 ? t[1] : t[2]));
-    if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
-    t[0] = t[1] = t[2] = 0.0;
+    if (lg) atomicAdd(&slot[kGSum + kg], g);
+    if (lm) atomicAdd(&slot[kMSum + km], mo);
+    if (lx) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]) + kx, mx);
+    g = 0.0;
+    mo = 0.0;
     mx = 0u;
   }
-  if (lane == 0) {
-    rec->sum[0] = t[0]; rec->sum[1] = t[1]; rec->sum[2] = t[2];
-    rec->max_bits = mx;
-  }
+  if (lg) rec->sum[kg] = g;
+  if (lm) rec->sum[3 + km] = mo;
+  if (lx) rec->max_bits[kx] = mx;
 }
 
 // wave 0, after the ticket's barrier: the records of the workgroup's waves -> the tensor's global slots
-__device__ __forceinline__ void ticket_stats_flush(const TicketRecord* recs, double* slot, int lane) {
-  static_assert(kWavesPerGroup == 8, "one record per lane of the first eight");
-  const TicketRecord& r = recs[lane & 7];
-  double t0 = r.sum[0], t1 = r.sum[1], t2 = r.sum[2];
-  uint32_t mx = r.max_bits;
-#pragma unroll
-  for (int o = 1; o <= 4; o <<= 1) {
-    t0 += __shfl_xor(t0, o, 64);
-    t1 += __shfl_xor(t1, o, 64);
-    t2 += __shfl_xor(t2, o, 64);
-    mx = max(mx, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx), o, 64)));
+template <int S>
+__device__ __forceinline__ void ticket_stats_flush(const TicketRecord<S>* recs, double* slot, int lane) {
+  static_assert(kWavesPerGroup == 8, "lane 8k + w takes value k of wave w's record");
+  asm volatile("" : "+v"(lane));
+  constexpr int kSums = S == 1 ? 9 : 3, kMaxima = S == 1 ? 3 : 1;
+  const TicketRecord<S>& r = recs[lane & 7];
+  const int k = lane >> 3;
+  const double x = octet_sum(k < kSums ? r.sum[k] : 0.0);  // sums 0..7
+  if ((lane & 7) == 0 && k < kSums) atomicAdd(&slot[kGSum + k], x);
+  if (S == 1) {
+    const double y = octet_sum(lane < 8 ? r.sum[kSums - 1] : 0.0);  // the ninth
+    if (lane == 0) atomicAdd(&slot[kGSum + 8], y);
   }
-  if (lane < 3) atomicAdd(&slot[kGSum + lane], lane == 0 ? t0 : (lane == 1 ? t1 : t2));
-  if (lane == 3) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]), mx);
+  const uint32_t mx = octet_max(k < kMaxima ? r.max_bits[k] : 0u);
+  if ((lane & 7) == 0 && k < kMaxima) atomicMax(reinterpret_cast<uint32_t*>(&slot[kMaxGM]) + k, mx);
 }
 
 // Correctly rounded square root for x = 0 or 2^-96 <= x <= 2^96: the hardware estimate is within
@@ -429,7 +467,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
                                               const float* Lreg, uint32_t l_base, const uint2* VQ, const float2* DEN,
                                               const uint32_t (&den_row)[2], const UpdateArgs& u, uint32_t q, int lane,
                                               uint32_t n_valid, LaneStats<STATS>& st) {
-  float sv_sum = 0.0f, sv_sq = 0.0f, sv_err = 0.0f;  // this quarter's part of the lane sums
+  float sv_err = 0.0f;  // this quarter's part of the lane's sum of squared quantization errors
 #pragma unroll
   for (int n = 0; n < 8; ++n) {
     const int i = n >> 2;
@@ -444,8 +482,6 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
       float vq = sn[i] * lds_at(Lreg, (c << 2) | l_base);
       if (TAIL && !is_valid(n, q, lane, n_valid)) vq = 0.0f;
       const float d = v[n] - vq;
-      sv_sum += v[n];
-      sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
       sv_err = __builtin_fmaf(d, d, sv_err);
     }
     const float mt = mq[n] * u.ibc1;
@@ -466,11 +502,7 @@ __device__ __forceinline__ void quant2_update(const float (&v)[8], const float (
       }
     }
   }
-  if (STATS == 1) {
-    st.add(kLVSum, lane, sv_sum);
-    st.add(kLVSq, lane, sv_sq);
-    st.add(kLVErr, lane, sv_err);
-  }
+  if (STATS == 1) st.add(kLVErr, lane, sv_err);
 }
 
 // ------------------------------------------------------------------ one quarter tile
@@ -632,6 +664,23 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (!is_valid(n, q, lane, n_valid)) { m[n] = 0.0f; v[n] = 0.0f; }
   }
 
+  if (STATS == 1) {
+    // the moments' sums and sums of squares, taken here where few other values are live (their quantization
+    // errors follow in the quantizer loops)
+    float sm_sum = 0.0f, sm_sq = 0.0f, sv_sum = 0.0f, sv_sq = 0.0f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      sm_sum += m[n];
+      sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
+      sv_sum += v[n];
+      sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
+    }
+    st.add(kLMSum, lane, sm_sum);
+    st.add(kLMSq, lane, sm_sq);
+    st.add(kLVSum, lane, sv_sum);
+    st.add(kLVSq, lane, sv_sq);
+  }
+
   // ---- parameters: issued here so that they arrive while the block maxima are reduced ----
   // Parameters and gradients are touched once per step: non-temporal accesses keep them from
   // displacing the code and scale lines in the caches (measured: both the load and the store of
@@ -670,7 +719,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     r = u2f(rb);
   }
   if (STATS == 1) {
-    st.max_bits(vL < 2 ? 0 : 1, lane, r);
+    st.max_moment(lane, r);
   }
   // a block whose maximum is below the smallest normal number is stored as all-zero
   const float sc_new = (r < FLT_MIN) ? 0.0f : r;
@@ -744,25 +793,19 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
 
   // ---- linear symmetric quantization of m; m is replaced by its quantized value ----
   if (wide_m) {
-    float sm_sum = 0.0f, sm_sq = 0.0f, sm_err = 0.0f;
+    float sm_err = 0.0f;
     uint32_t kept[8];
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const float mq = bmo == 32 ? m[n] : bf16_rne(m[n]);  // pads are 0 and stay 0
       if (STATS == 1) {
         const float dd = m[n] - mq;
-        sm_sum += m[n];
-        sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
         sm_err = __builtin_fmaf(dd, dd, sm_err);
       }
       m[n] = mq;
       kept[n] = f2u(mq);
     }
-    if (STATS == 1) {
-      st.add(kLMSum, lane, sm_sum);
-      st.add(kLMSq, lane, sm_sq);
-      st.add(kLMErr, lane, sm_err);
-    }
+    if (STATS == 1) st.add(kLMErr, lane, sm_err);
     if (bmo == 32) {
 #pragma unroll
       for (int n = 0; n < 8; ++n) CMO[n * 64u + ul] = kept[n];
@@ -781,7 +824,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
     const float qmaxf = static_cast<float>(qmax);
     const uint32_t r_base = 4u << bmo;
     uint32_t code[8];
-    float sm_sum = 0.0f, sm_sq = 0.0f, sm_err = 0.0f;  // this quarter's part of the lane sums
+    float sm_err = 0.0f;  // this quarter's part of the lane's sum of squared quantization errors
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int i = n >> 2;
@@ -797,31 +840,23 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       if (STATS == 1) {
         if (TAIL && !is_valid(n, q, lane, n_valid)) mq = 0.0f;
         const float dd = m[n] - mq;
-        sm_sum += m[n];
-        sm_sq = __builtin_fmaf(m[n], m[n], sm_sq);
         sm_err = __builtin_fmaf(dd, dd, sm_err);
       }
       m[n] = mq;
     }
-    if (STATS == 1) {
-      st.add(kLMSum, lane, sm_sum);
-      st.add(kLMSq, lane, sm_sq);
-      st.add(kLMErr, lane, sm_err);
-    }
+    if (STATS == 1) st.add(kLMErr, lane, sm_err);
     STQ_SWITCH_BITS(bmo, (pack_store<B>(code, CMO, s0mo, carry_m, ul)));
   }
 
   // ---- logarithmic quantization of v and the parameter update ----
   if (wide_v) {
-    float sv_sum = 0.0f, sv_sq = 0.0f, sv_err = 0.0f;
+    float sv_err = 0.0f;
     uint32_t kept[8];
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const float vq = bvo == 32 ? v[n] : bf16_rne(v[n]);
       if (STATS == 1) {
         const float dd = v[n] - vq;
-        sv_sum += v[n];
-        sv_sq = __builtin_fmaf(v[n], v[n], sv_sq);
         sv_err = __builtin_fmaf(dd, dd, sv_err);
       }
       kept[n] = f2u(vq);
@@ -830,11 +865,7 @@ __device__ __forceinline__ void process_quarter(const TensorDesc& d, uint32_t ti
       const float den = __builtin_sqrtf(vt) + ua.eps;
       theta[n] = updated_param<false>(theta[n], mt, den, 0.0f, ua);
     }
-    if (STATS == 1) {
-      st.add(kLVSum, lane, sv_sum);
-      st.add(kLVSq, lane, sv_sq);
-      st.add(kLVErr, lane, sv_err);
-    }
+    if (STATS == 1) st.add(kLVErr, lane, sv_err);
     if (bvo == 32) {
 #pragma unroll
       for (int n = 0; n < 8; ++n) CVO[n * 64u + ul] = kept[n];
@@ -913,19 +944,20 @@ __device__ __forceinline__ uint32_t desc_tile_begin(const TensorDesc* table, uin
 //    memory system gives 10-15 % more bandwidth to this than to waves that each walk their own stripe of the
 //    arrays at their own pace; on small ones the barrier costs more than the order gains.
 //  * stripes (a.sched null): wave w of W takes the chunks w, w+W, w+2W, ... of `chunk` consecutive units.
-//    The variant that collects every statistic uses it with one chunk per wave (a contiguous range: it
-//    flushes its sums once per tensor a wave has touched), small launches with chunk 1.
+//    The variants that collect statistics use it with few, long chunks (a wave flushes its sums to the
+//    tensor's global slots whenever its next unit lies in another tensor), the plain one with chunk 1 or 4.
 // The ticket counter resets itself: the last workgroup to leave the kernel clears it (and the count of
 // workgroups that have left), so every launch -- also a replayed one -- finds both at zero.
-// STATS 1 (all statistics) needs about 30 more registers and 76 KB of LDS: two workgroups per CU.
-// STATS 2 (the gradient's statistics only) stays within the plain kernel's register and LDS budget.
+// STATS 1 (all statistics) and 2 (the gradient's only) stay within the plain kernel's budget of 80 registers
+// and a third of a CU's LDS: their running sums live in LDS and nothing derived from the lane index is kept
+// across the tile loop (see LaneStats).  Only the wide-state variant (MODE 2) runs two workgroups per CU.
 template <bool BF16, int STATS, int MODE>
-__global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 : 6) void step_kernel(const StepArgs a) {
+__global__ __launch_bounds__(64 * kWavesPerGroup, MODE == 2 ? 4 : 6) void step_kernel(const StepArgs a) {
   constexpr int kWaves = kWavesPerGroup;
   __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsWords + kWavesPerGroup * LaneStats<STATS>::kWords];
   __shared__ uint32_t drawn[2];  // the ticket being worked on and the next one, alternating
-  // gradient statistics of the two tickets in flight, one record per wave (STATS 2 with tickets)
-  __shared__ TicketRecord ticket_rec[2][kWavesPerGroup];
+  // statistics of the two tickets in flight, one record per wave
+  __shared__ TicketRecord<STATS> ticket_rec[2][kWavesPerGroup];
   const bool tickets = a.sched != nullptr;
   if (threadIdx.x == 0) drawn[0] = blockIdx.x;
   // the value tables of every width (4 KB), the search table of the second-moment widths this launch can write
@@ -989,7 +1021,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
         have_desc = true;
       }
       if (t >= d.tile_begin + d.n_tiles) {  // t < total_tiles, so a later tensor holds it
-        if (STATS && !(STATS == 2 && tickets)) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+        if (STATS && !tickets) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
         do {
           ++l;
           d = load_desc(a.desc, l);
@@ -1008,8 +1040,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
           process_quarter<BF16, STATS, true, MODE>(d, tile, q, static_cast<uint32_t>(left), a, lds, ws, lane, carry_m,
                                                    carry_v, st);
       }
-      if (STATS == 2 && tickets) {
-        if constexpr (STATS == 2) {
+      if (STATS && tickets) {
+        if constexpr (STATS != 0) {
           // does the ticket's first unit lie in this wave's tensor?  (it cannot lie behind it: units only grow)
           const uint32_t t_first = static_cast<uint32_t>((c_begin - wave) >> qs);
           ticket_stats_tile(st, &ticket_rec[turn][wave], t_first >= d.tile_begin, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
@@ -1019,20 +1051,21 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, (STATS == 1 || MODE == 2) ? 4 
       }
     }
     if (tickets) {
-      if constexpr (STATS == 2) {
+      if constexpr (STATS != 0) {
         // a wave without a unit in this ticket (the launch's last one) leaves an empty record
-        if (c_begin >= c_end && lane < 4) reinterpret_cast<double*>(&ticket_rec[turn][wave])[lane] = 0.0;
+        constexpr int kRecordDoubles = sizeof(TicketRecord<STATS>) / 8;
+        if (c_begin >= c_end && lane < kRecordDoubles) reinterpret_cast<double*>(&ticket_rec[turn][wave])[lane] = 0.0;
       }
       if (threadIdx.x == 0) drawn[turn ^ 1u] = next_ticket;
       __syncthreads();  // the workgroup goes on together
-      if constexpr (STATS == 2) {
+      if constexpr (STATS != 0) {
         // wave 0 worked on the ticket's first unit: its l is that unit's tensor
         if (wave == 0) ticket_stats_flush(ticket_rec[turn], a.stats + static_cast<size_t>(l) * kStatSlots, lane);
       }
       turn ^= 1u;
     }
   }
-  if (STATS && !(STATS == 2 && tickets) && have_desc) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
+  if (STATS && !tickets && have_desc) flush_stats(st, a.stats + static_cast<size_t>(l) * kStatSlots, lane);
   if (tickets && threadIdx.x == 0) {
     // every ticket this workgroup drew precedes its leaving; the last one to leave has seen all others leave
     const uint32_t left_before = __hip_atomic_fetch_add(a.sched + 1, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
