@@ -112,6 +112,20 @@ def check_window(oracle, dm, w, l, lo, n, th_ref, st_ref, tag):
     assert np.array_equal(th.view(np.uint32), th_ref.view(np.uint32)), f"{tag}: params not bit-equal"
 
 
+def all_stats_close(g, o, tag):
+    """Device statistics of a tensor against the oracle's: counts and maxima equal, the gradient's sums (fp64 on
+    both sides) to 1e-12, the moments' sums (fp32 partial sums on the device) to 1e-5 plus the underflow floor."""
+    assert g.count == o.count, tag
+    for name in ("g_absmax", "m_absmax", "v_absmax"):
+        assert getattr(g, name) == getattr(o, name), f"{tag} {name}"
+    for name, scale in (("g_sum", o.g_abs_sum), ("g_abs_sum", o.g_abs_sum), ("g_sq_sum", o.g_sq_sum)):
+        assert abs(getattr(g, name) - getattr(o, name)) <= 1e-12 * scale, f"{tag} {name}"
+    for name, scale in (("m_sum", np.sqrt(o.m_sq_sum * o.count)), ("m_sq_sum", o.m_sq_sum), ("m_err_sq", o.m_err_sq),
+                        ("v_sum", o.v_sum), ("v_sq_sum", o.v_sq_sum), ("v_err_sq", o.v_err_sq)):
+        a, b = getattr(g, name), getattr(o, name)
+        assert abs(a - b) <= 1e-5 * scale + o.count * 1.2e-38, f"{tag} {name}: {a} vs {b}"
+
+
 @pytest.mark.parametrize("name", ["gpt2-small", "vit-b16", "gpt2-xl", "llama7b-slice"])
 def test_full_size_sampled_parity(oracle, name):
     """Every tensor of the workload is covered: the small and medium ones whole, at least 1 % of each
@@ -132,7 +146,7 @@ def test_full_size_sampled_parity(oracle, name):
         before = [window_state(oracle, dm, w, l, lo, n) for l, lo, n in windows]
         dm.step(t, stats=want_stats)
         torch.cuda.synchronize()
-        parallel(lambda x: oracle.step(x[0], x[1], x[2], **w.hparams, t=t), before)
+        ostats = parallel(lambda x: oracle.step(x[0], x[1], x[2], **w.hparams, t=t, want_stats=want_stats), before)
         for (l, lo, n), (th, g, st) in zip(windows, before):
             check_window(oracle, dm, w, l, lo, n, th, st, f"{name} step {t} tensor {l} window {lo}+{n}")
         print(f"{name}: step {t} compared", flush=True)
@@ -150,6 +164,12 @@ def test_full_size_sampled_parity(oracle, name):
                 assert gs[l].v_absmax == float(dm.v_scales[l].max())
                 assert gs[l].m_err_sq <= gs[l].m_sq_sum and gs[l].v_err_sq <= gs[l].v_sq_sum
                 del g64
+            # the tensors that one window covers whole: all thirteen statistics against the oracle's
+            whole = [(l, o) for (l, lo, n), o in zip(windows, ostats) if lo == 0 and n == w.tensors[l][1]]
+            assert whole
+            for l, o in whole:
+                all_stats_close(gs[l], o, f"{name} tensor {l}")
+            print(f"{name}: statistics of {len(whole)} whole tensors compared", flush=True)
     ctx.close()
     del dm
     torch.cuda.empty_cache()

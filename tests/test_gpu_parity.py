@@ -430,8 +430,8 @@ def test_repack_rejects_wide_widths(ctx):
     assert stq.state_bytes(n, 128, 16)[0] == 2 * 64 * 16 * 4 and stq.state_bytes(n, 128, 32)[0] == 2 * 64 * 32 * 4
 
 
-@pytest.mark.parametrize("tickets", [False, True])
-def test_many_small_tensors_in_one_launch(oracle, tickets):
+@pytest.mark.parametrize("tickets,kind", [(False, True), (True, "grad"), (True, True)])
+def test_many_small_tensors_in_one_launch(oracle, tickets, kind):
     # 1500 tensors of 1..5000 elements: every wave walks over many tensor boundaries and ragged tiles;
     # with the ticket schedule every ticket of eight neighbouring tiles spans several tensors
     rng = np.random.default_rng(77)
@@ -447,13 +447,13 @@ def test_many_small_tensors_in_one_launch(oracle, tickets):
     st_ref = oracle_states(oracle, w, plan)
     for t in (1, 2):
         dm.set_grads(t)
-        dm.step(t, stats=("grad" if tickets else True) if t == 2 else False)
+        dm.step(t, stats=kind if t == 2 else False)
         torch.cuda.synchronize()
         gs = c.stats(L, dm.stream) if t == 2 else None
         for l in range(L):
             s = oracle.step(th_ref[l], dm.host_grad(l), st_ref[l], **w.hparams, t=t, want_stats=True)
             if gs is not None and (l % 13 == 0 or tickets):
-                if tickets:   # the gradient's statistics only
+                if kind == "grad":   # the gradient's statistics only
                     assert abs(gs[l].g_sq_sum - s.g_sq_sum) <= 1e-12 * s.g_sq_sum and gs[l].g_absmax == s.g_absmax, l
                     assert abs(gs[l].g_abs_sum - s.g_abs_sum) <= 1e-12 * s.g_abs_sum, l
                     assert abs(gs[l].g_sum - s.g_sum) <= 1e-12 * s.g_abs_sum, l
@@ -476,7 +476,7 @@ def ticket_ctx(ctx):
 
 @pytest.mark.parametrize("seed", range(12))
 def test_random_workloads_ticket_schedule(oracle, ticket_ctx, seed):
-    test_random_workloads(oracle, ticket_ctx, seed, grad_stats_only=True)
+    test_random_workloads(oracle, ticket_ctx, seed, grad_stats_only=True)   # every other statistics step: all of them
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -503,7 +503,7 @@ def test_random_workloads(oracle, ctx, seed, grad_stats_only=False):
         dm.set_grads(t)
         want_stats = bool(rng.integers(0, 2))
         if want_stats and grad_stats_only and t % 2 == 0:
-            want_stats = "grad"   # under tickets this variant reduces per ticket and workgroup
+            want_stats = "grad"
         if t == switch_at:
             new = [(int(rng.choice(widths)), int(rng.choice(widths))) for _ in range(L)]
             dm.step_transition(t, new, stats=want_stats)
@@ -651,3 +651,24 @@ def test_grad_stats_pass_shows_non_finite_gradients(oracle, ctx, dtype):
     assert got[0].g_absmax == float("inf") == want[0].g_absmax
     assert not np.isfinite(got[1].g_sq_sum) and not np.isfinite(want[1].g_sq_sum)
     assert np.isfinite(got[2].g_sq_sum) and abs(got[2].g_sq_sum - want[2].g_sq_sum) <= 1e-12 * want[2].g_sq_sum
+
+
+# ------------------------------------------ every statistic under the ticket schedule
+# (records of all thirteen values per wave and ticket; the launches here are small, so the schedule is forced)
+def test_degenerate_values_ticket_schedule(oracle, ticket_ctx):
+    test_degenerate_values(oracle, ticket_ctx)
+
+
+@pytest.mark.parametrize("dtype,K", [("bf16", 64), ("fp32", 256)])
+def test_step_transition_every_width_pair_ticket_schedule(oracle, ticket_ctx, dtype, K):
+    test_step_transition_every_width_pair(oracle, ticket_ctx, dtype, K)
+
+
+@pytest.mark.parametrize("dtype,K", [("fp32", 128), ("bf16", 64)])
+def test_wide_states_every_combination_ticket_schedule(oracle, ticket_ctx, dtype, K):
+    test_wide_states_every_combination(oracle, ticket_ctx, dtype, K)
+
+
+@pytest.mark.parametrize("dtype,K", [("bf16", 128)])
+def test_transitions_among_the_papers_widths_ticket_schedule(oracle, ticket_ctx, dtype, K):
+    test_transitions_among_the_papers_widths(oracle, ticket_ctx, dtype, K)
