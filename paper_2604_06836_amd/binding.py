@@ -10,6 +10,8 @@ import ctypes as C
 import os
 from typing import Iterable, Optional, Sequence
 
+import numpy as np
+
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("STQ_LIBRARY", os.path.join(_PKG, "libstq.so"))  # override: another build of the same ABI
 
@@ -64,6 +66,14 @@ class DecideCfg(C.Structure):
 class RepackJob(C.Structure):
     _fields_ = [("numel", C.c_uint64), ("src_codes", C.c_void_p), ("dst_codes", C.c_void_p),
                 ("state", C.c_uint8), ("src_bits", C.c_uint8), ("dst_bits", C.c_uint8)]
+
+
+# the same records as numpy dtypes, for callers that build or patch whole arrays at once
+REPACK_JOB_DTYPE = np.dtype([("numel", "<u8"), ("src_codes", "<u8"), ("dst_codes", "<u8"),
+                             ("state", "u1"), ("src_bits", "u1"), ("dst_bits", "u1")], align=True)
+TENSOR_DTYPE = np.dtype([("param", "<u8"), ("grad", "<u8"), ("numel", "<u8"), ("m_codes", "<u8"), ("m_scales", "<u8"),
+                         ("v_codes", "<u8"), ("v_scales", "<u8")])
+BITS_DTYPE = np.dtype([("m_bits", "u1"), ("v_bits", "u1")])
 
 
 class Codes(C.Structure):
@@ -241,10 +251,15 @@ class Context:
         return out
 
     def repack_many(self, jobs, block: int, stream: int = 0):
-        """jobs: sequence of (numel, state, src_ptr, src_bits, dst_ptr, dst_bits)."""
-        arr = (RepackJob * len(jobs))()
-        for i, (numel, state, src, sb, dst, db) in enumerate(jobs):
-            arr[i] = RepackJob(numel, src, dst, state, sb, db)
+        """jobs: sequence of (numel, state, src_ptr, src_bits, dst_ptr, dst_bits), or a numpy array of
+        REPACK_JOB_DTYPE records (the C struct's layout), which is passed as it is."""
+        if isinstance(jobs, np.ndarray):
+            assert jobs.dtype == REPACK_JOB_DTYPE and jobs.flags["C_CONTIGUOUS"]
+            arr = jobs.ctypes.data_as(C.POINTER(RepackJob))
+        else:
+            arr = (RepackJob * len(jobs))()
+            for i, (numel, state, src, sb, dst, db) in enumerate(jobs):
+                arr[i] = RepackJob(numel, src, dst, state, sb, db)
         _check(self._lib.stq_repack_many(self._h, arr, len(jobs), block, C.c_void_p(stream)), "stq_repack_many")
 
     def repack(self, numel: int, block: int, state: int, src: int, src_bits: int, dst: int, dst_bits: int,

@@ -38,6 +38,8 @@ class DeviceModel:
         self.m_scales: List[torch.Tensor] = []
         self.v_scales: List[torch.Tensor] = []
         self._spare, self._cw = {}, {}     # (tensor, state) -> spare code buffer; cache of code sizes
+        self._whole = None                 # address tables of the all-at-once path of apply_plan (spare_width only)
+        self._spare_width = spare_width
         self.numel = [n for _, n in w.tensors]
         gdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
         for l, (_, n) in enumerate(w.tensors):
@@ -105,6 +107,7 @@ class DeviceModel:
         return out
 
     def _adopt(self, changes, new_plan, new_cplan, also_patch):
+        self._whole = None
         arrays = (self.tensors,) + tuple(also_patch)
         for l, state, cur, b0, b1, dst, ptr in changes:
             self._spare[(l, state)] = cur[l]
@@ -123,6 +126,9 @@ class DeviceModel:
         (the buffer the state used before) so that a loop of transitions allocates nothing once warm.
         `also_patch`: further ctypes tensor arrays (other gradient sets of the same model) whose
         code pointers follow."""
+        if batched and self._spare_width and max(max(p) for p in new_plan) <= self._spare_width:
+            return self._apply_plan_whole(new_plan, also_patch)
+        self._whole = None
         changes = self._destinations(new_plan)
         jobs = [(self.numel[l], state, cur[l].data_ptr(), b0, ptr, b1) for l, state, cur, b0, b1, dst, ptr in changes]
         if batched and jobs:
@@ -132,6 +138,42 @@ class DeviceModel:
                 self.ctx.repack(n, self.w.K, state, src, b0, dst, b1, self.stream)
         self._adopt(changes, new_plan, binding.make_plan(new_plan), also_patch)
         return len(changes)
+
+    def _apply_plan_whole(self, new_plan, also_patch) -> int:
+        """apply_plan when every state has both of its buffers at full capacity (spare_width): the job table
+        and the patched tensor arrays are built with array operations instead of a Python loop per change."""
+        if self._whole is None:
+            L = len(self.numel)
+            self._whole = dict(
+                cur=[np.array([t.data_ptr() for t in lst], np.uint64) for lst in (self.m_codes, self.v_codes)],
+                spare=[np.array([self._spare[(l, st)].data_ptr() for l in range(L)], np.uint64) for st in (0, 1)],
+                numel=np.array(self.numel, np.uint64), plan=np.array(self.plan, np.uint8))
+        wh = self._whole
+        new = np.asarray(new_plan, np.uint8)
+        idx = [np.nonzero(wh["plan"][:, st] != new[:, st])[0] for st in (0, 1)]
+        jobs = np.zeros(len(idx[0]) + len(idx[1]), binding.REPACK_JOB_DTYPE)
+        at = 0
+        for st in (0, 1):
+            j = jobs[at:at + len(idx[st])]
+            j["numel"], j["src_codes"], j["dst_codes"] = wh["numel"][idx[st]], wh["cur"][st][idx[st]], wh["spare"][st][idx[st]]
+            j["state"], j["src_bits"], j["dst_bits"] = st, wh["plan"][idx[st], st], new[idx[st], st]
+            at += len(idx[st])
+        if len(jobs):
+            self.ctx.repack_many(jobs, self.w.K, self.stream)
+        views = [np.frombuffer(arr, dtype=binding.TENSOR_DTYPE) for arr in (self.tensors,) + tuple(also_patch)]
+        for st, (lst, field) in enumerate(((self.m_codes, "m_codes"), (self.v_codes, "v_codes"))):
+            i = idx[st]
+            wh["cur"][st][i], wh["spare"][st][i] = wh["spare"][st][i], wh["cur"][st][i].copy()
+            for v in views:
+                v[field][i] = wh["cur"][st][i]
+            for l in i.tolist():   # the tensor objects follow their addresses
+                lst[l], self._spare[(l, st)] = self._spare[(l, st)], lst[l]
+        wh["plan"] = new.copy()
+        self.plan = [tuple(p) for p in new.tolist()]
+        self.cplan = (binding.Bits * len(self.plan))()
+        np.frombuffer(self.cplan, dtype=binding.BITS_DTYPE)["m_bits"][:] = new[:, 0]
+        np.frombuffer(self.cplan, dtype=binding.BITS_DTYPE)["v_bits"][:] = new[:, 1]
+        return len(jobs)
 
     def step_transition(self, t: int, new_plan: Sequence[Tuple[int, int]], stats=False, also_patch=()) -> int:
         """One step that reads the states at the current plan and writes them at new_plan
