@@ -284,6 +284,7 @@ def main():
         one_step(t, False)
     torch.cuda.synchronize()
     repacked = 0
+    dm.repack_bytes = 0
     t0 = time.perf_counter()
     for _ in range(steps):
         t += 1
@@ -313,6 +314,7 @@ def main():
         "config": {"workload": w.name, "configs_index": w.cfg, "params": n, "tensors": L, "block": w.K,
                    "grad_dtype": w.grad_dtype, "avg_state_bits": round(w.avg_bits(plan), 3),
                    "transition": args.transition, "changed_states_in_timed_region": repacked,
+                   "repack_bytes_in_timed_region": dm.repack_bytes,
                    "statistics": ("gradient" if (args.stats == "grad" or use_engine) else "all")
                    if decide_every_step else "none"},
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -4,6 +4,8 @@
 // The step kernel itself is in stq_step.hip.
 #include <hip/hip_runtime.h>
 
+#include <utility>
+
 #include <cstdint>
 
 #include "stq_device.h"
@@ -79,30 +81,48 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
 }
 
 // The lane's 32 codes of width B out of / into its B stream words; all shifts are compile-time.
+// Pointers that arrive through the job table are loaded from memory, so the compiler cannot see that they
+// are global; say so, to get global_load/global_store instead of flat accesses.
+#define STQ_GLOBAL __attribute__((address_space(1)))
+// Bits [SH, SH+B) of x in one instruction (from the plain expression the compiler makes a shift and a mask).
+template <int SH, int B>
+__device__ __forceinline__ uint32_t bit_field(uint32_t x) {
+  uint32_t r;
+  asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "n"(SH), "n"(B));
+  return r;
+}
+// code N of a lane's stream words
+template <int B, int N>
+__device__ __forceinline__ uint32_t extract(const uint32_t (&w)[B]) {
+  constexpr int off = N * B, p = off >> 5, sh = off & 31;
+  if constexpr (sh + B <= 32) {
+    return bit_field<sh, B>(w[p]);
+  } else {  // a code that straddles two words: align it first
+    return bit_field<0, B>(__builtin_amdgcn_alignbit(w[p + 1], w[p], static_cast<uint32_t>(sh)));
+  }
+}
+template <int B, int... N>
+__device__ __forceinline__ void extract_all(const uint32_t (&w)[B], uint32_t (&code)[32], std::integer_sequence<int, N...>) {
+  ((code[N] = extract<B, N>(w)), ...);
+}
 template <int B>
-__device__ __forceinline__ void unpack32(const uint32_t* src, uint32_t (&code)[32]) {
+__device__ __forceinline__ void unpack32(const STQ_GLOBAL uint32_t* src, uint32_t (&code)[32]) {
   uint32_t w[B];
 #pragma unroll
   for (int p = 0; p < B; ++p) w[p] = src[64 * p];
-  constexpr uint32_t mask = (1u << B) - 1u;
-#pragma unroll
-  for (int n = 0; n < 32; ++n) {
-    const int off = n * B, p = off >> 5, sh = off & 31;
-    if (sh + B <= 32) code[n] = (w[p] >> sh) & mask;
-    else code[n] = ((w[p] >> sh) | (w[p + 1] << (32 - sh))) & mask;
-  }
+  extract_all<B>(w, code, std::make_integer_sequence<int, 32>{});
 }
 
 template <int B>
-__device__ __forceinline__ void pack32(const uint32_t (&code)[32], uint32_t* dst) {
+__device__ __forceinline__ void pack32(const uint32_t (&code)[32], STQ_GLOBAL uint32_t* dst) {
   uint32_t w[B];
 #pragma unroll
   for (int p = 0; p < B; ++p) w[p] = 0u;
 #pragma unroll
   for (int n = 0; n < 32; ++n) {
     const int off = n * B, p = off >> 5, sh = off & 31;
-    w[p] |= code[n] << sh;
-    if (sh + B > 32) w[p + 1] |= code[n] >> (32 - sh);
+    if (sh == 0) w[p] = code[n]; else w[p] |= code[n] << sh;
+    if (sh + B > 32) w[p + 1] = code[n] >> (32 - sh);  // first bits of the next word
   }
 #pragma unroll
   for (int p = 0; p < B; ++p) dst[64 * p] = w[p];
@@ -136,16 +156,18 @@ __device__ __forceinline__ uint32_t job_tile_begin(const RepackJob* table, uint3
   return *(const STQ_CONSTANT uint32_t*)(&table[j].tile_begin);
 }
 
-// Many width changes in one launch.  Wave w of W takes the chunks w, w+W, ... of kRepackChunk
-// consecutive tiles of the launch-wide tile order; when it enters a job with another conversion
-// table it reloads its LDS slice.
+// Many width changes in one launch.  One wave per workgroup; wave w of W takes the chunks w, w+W, ... of
+// kRepackChunk consecutive tiles of the launch-wide tile order; when it enters a job with another conversion
+// table it reloads its table.  The table sits at LDS address 0 as 256 bytes (new codes have at most 8 bits), so
+// an old code is the address of its new code as it comes out of the bit-field extraction: one vector
+// instruction per code to unpack, none to look up, one to pack -- the kernel moves (b_old + b_new)/8 bytes per
+// element and was bound by instruction issue with a word table behind a per-wave base address.
 constexpr uint32_t kRepackChunk = 8;
-__global__ __launch_bounds__(256) void repack_many_kernel(const RepackManyArgs a) {
-  __shared__ uint32_t lut_all[4][256];
-  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t* lut = lut_all[wave];
-  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * 4;
-  uint64_t base = (static_cast<uint64_t>(blockIdx.x) * 4 + wave) * kRepackChunk;
+__global__ __launch_bounds__(64) void repack_many_kernel(const RepackManyArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[256];  // the kernel's only LDS variable: address 0
+  const uint32_t lane = threadIdx.x;
+  const uint64_t n_waves = gridDim.x;
+  uint64_t base = static_cast<uint64_t>(blockIdx.x) * kRepackChunk;
   if (base >= a.total_tiles) return;
   // job holding the first tile: last j with tile_begin <= base
   uint32_t lo = 0, hi = a.n_jobs - 1;
@@ -162,15 +184,17 @@ __global__ __launch_bounds__(256) void repack_many_kernel(const RepackManyArgs a
     const uint32_t b_old = job.b_old, b_new = job.b_new, which = job.lut;
     if (loaded != which) {
       __builtin_amdgcn_wave_barrier();  // the previous tile's table reads are done (same wave, in order)
-      for (uint32_t k = lane; k < 256; k += 64) lut[k] = a.luts[which * 256 + k];
+      // lane k packs entries 4k .. 4k+3 of the word table in device memory into one LDS word
+      const uint4 e = *reinterpret_cast<const uint4*>(a.luts + which * 256 + 4 * lane);
+      reinterpret_cast<uint32_t*>(lut)[lane] = e.x | (e.y << 8) | (e.z << 16) | (e.w << 24);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       loaded = which;
     }
     const uint64_t tile = t - job.tile_begin;
-    const uint32_t* src = job.src + tile * 64 * b_old + lane;
-    uint32_t* dst = job.dst + tile * 64 * b_new + lane;
+    const STQ_GLOBAL uint32_t* src = (const STQ_GLOBAL uint32_t*)(job.src + tile * 64 * b_old + lane);
+    STQ_GLOBAL uint32_t* dst = (STQ_GLOBAL uint32_t*)(job.dst + tile * 64 * b_new + lane);
     uint32_t code[32];
     STQ_SWITCH_WIDTH(b_old, (unpack32<B>(src, code)));
 #pragma unroll
@@ -178,9 +202,13 @@ __global__ __launch_bounds__(256) void repack_many_kernel(const RepackManyArgs a
     const uint64_t left = job.numel - tile * kTile;
     if (left < static_cast<uint64_t>(kTile)) {  // ragged last tile: pad codes are 0
       const uint32_t n_valid = static_cast<uint32_t>(left);
+      // (the element offsets are computed here, where they are needed: derived from the plain lane index
+      // they would be hoisted out of the loops and occupy two dozen registers throughout)
+      uint32_t first = 4u * lane;
+      asm volatile("" : "+v"(first));
 #pragma unroll
       for (int n = 0; n < 32; ++n)
-        if (256u * (n >> 2) + 4u * lane + (n & 3) >= n_valid) code[n] = 0u;
+        if (256u * (n >> 2) + first + (n & 3) >= n_valid) code[n] = 0u;
     }
     STQ_SWITCH_WIDTH(b_new, (pack32<B>(code, dst)));
    }
@@ -314,7 +342,7 @@ int launch_repack(const RepackArgs& a, void* stream) {
 }
 
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream) {
-  hipLaunchKernelGGL(repack_many_kernel, dim3(groups), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  hipLaunchKernelGGL(repack_many_kernel, dim3(groups), dim3(64), 0, static_cast<hipStream_t>(stream), a);
   return static_cast<int>(hipGetLastError());
 }
 

@@ -39,6 +39,7 @@ class DeviceModel:
         self.v_scales: List[torch.Tensor] = []
         self._spare, self._cw = {}, {}     # (tensor, state) -> spare code buffer; cache of code sizes
         self._whole = None                 # address tables of the all-at-once path of apply_plan (spare_width only)
+        self.repack_bytes = 0              # code bytes read and written by the re-pack launches so far
         self._spare_width = spare_width
         self.numel = [n for _, n in w.tensors]
         gdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
@@ -131,6 +132,7 @@ class DeviceModel:
         self._whole = None
         changes = self._destinations(new_plan)
         jobs = [(self.numel[l], state, cur[l].data_ptr(), b0, ptr, b1) for l, state, cur, b0, b1, dst, ptr in changes]
+        self.repack_bytes += sum(((n + 2047) // 2048) * 256 * (b0 + b1) for n, _, _, b0, _, b1 in jobs)
         if batched and jobs:
             self.ctx.repack_many(jobs, self.w.K, self.stream)
         else:
@@ -160,6 +162,8 @@ class DeviceModel:
             at += len(idx[st])
         if len(jobs):
             self.ctx.repack_many(jobs, self.w.K, self.stream)
+            tiles = (jobs["numel"] + np.uint64(2047)) // np.uint64(2048)
+            self.repack_bytes += int((tiles * 256 * (jobs["src_bits"].astype(np.uint64) + jobs["dst_bits"])).sum())
         views = [np.frombuffer(arr, dtype=binding.TENSOR_DTYPE) for arr in (self.tensors,) + tuple(also_patch)]
         for st, (lst, field) in enumerate(((self.m_codes, "m_codes"), (self.v_codes, "v_codes"))):
             i = idx[st]
