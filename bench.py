@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+ALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12  # vector lanes x peak clock: 39.3 T lane-instructions/s
 
 
 def block_slices(n, K, parts):
@@ -332,8 +333,15 @@ def main():
         tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ("-engine-alg1" if use_engine else "")))
         if tr and tr.get("kernel_source_sha256") == src_hash:
             out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
-            if "valu_busy" in tr:
-                out["roofline"]["valu_busy"] = tr["valu_busy"]
+            if "valu_insts_per_param" in tr:
+                # The second roof of this kernel: vector instructions.  One fp32 VALU instruction per lane and
+                # cycle on 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz (the published 157.3 TFLOP/s counts packed
+                # fused multiply-adds, four flops per lane and cycle, which this arithmetic contract rules out).
+                lane_insts = tr["valu_insts_per_param"] * n / (k_avg_ms * 1e-3) / 1e12
+                out["roofline"]["alu"] = {"valu_insts_per_param": tr["valu_insts_per_param"], "achieved": lane_insts,
+                                          "peak": ALU_PEAK_TLANE, "unit": "T lane-instructions/s",
+                                          "frac": lane_insts / ALU_PEAK_TLANE, "valu_busy": tr.get("valu_busy"),
+                                          "shader_clock_ghz": tr.get("shader_clock_ghz")}
         elif tr:
             out["roofline"]["traffic_note"] = "profiles/step_kernel_traffic.json holds counters of another version of the kernel (%s)" % tr.get("kernel_source_sha256")
     if not args.no_cpu_baseline:
