@@ -588,8 +588,8 @@ int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32
   a.n_jobs = n;
   a.total_tiles = static_cast<uint32_t>(total);
   a.luts = ctx->d_luts;
-  // one wave per workgroup, chunks of eight tiles (kRepackChunk); at most eight waves per SIMD resident
-  const uint64_t need = (total + 7) / 8;
+  // one wave per workgroup, chunks of kRepackChunk tiles; at most eight waves per SIMD resident
+  const uint64_t need = (total + kRepackChunk - 1) / kRepackChunk;
   const uint64_t cap = static_cast<uint64_t>(ctx->n_cu) * 32;
   return launch_repack_many(a, static_cast<uint32_t>(need < cap ? need : cap), stream) == 0 ? STQ_OK : STQ_EHIP;
 }

@@ -5,6 +5,7 @@
 namespace stq {
 
 constexpr int kTile = 2048;         // elements per tile = 64 lanes x 32 codes
+constexpr uint32_t kRepackChunk = 8;  // consecutive tiles a wave of repack_many_kernel converts at a time (1..16 measured alike)
 constexpr int kWavesPerGroup = 8;   // 512-thread workgroups
 constexpr int kStatSlots = 16;      // 8-byte accumulator slots per tensor
 constexpr uint32_t kSchedWords = 2;  // the ticket counter of a launch and the count of workgroups that have left

@@ -162,7 +162,6 @@ __device__ __forceinline__ uint32_t job_tile_begin(const RepackJob* table, uint3
 // an old code is the address of its new code as it comes out of the bit-field extraction: one vector
 // instruction per code to unpack, none to look up, one to pack -- the kernel moves (b_old + b_new)/8 bytes per
 // element and was bound by instruction issue with a word table behind a per-wave base address.
-constexpr uint32_t kRepackChunk = 8;
 __global__ __launch_bounds__(64) void repack_many_kernel(const RepackManyArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[256];  // the kernel's only LDS variable: address 0
   const uint32_t lane = threadIdx.x;
