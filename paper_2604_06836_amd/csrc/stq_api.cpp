@@ -521,28 +521,16 @@ int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* stream) {
 
 int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state, const void* src,
                uint32_t src_bits, void* dst, uint32_t dst_bits, void* stream) {
-  if (!ctx || !src || !dst || numel == 0 || (state != 0 && state != 1)) return STQ_EINVAL;
-  if (lg_block(block) < 0) return STQ_EBLOCK;
-  if (int e = check_bits(src_bits)) return e;
-  if (int e = check_bits(dst_bits)) return e;
-  if (!aligned(src, 256) || !aligned(dst, 256)) return STQ_EALIGN;
-  const uint64_t tiles = (numel + kTile - 1) / kTile;
-  if (tiles > 0x3FFFFFFull) return STQ_EINVAL;
-  // overlap check on the byte ranges
-  const uintptr_t s0 = reinterpret_cast<uintptr_t>(src), s1 = s0 + tiles * 256 * src_bits;
-  const uintptr_t d0 = reinterpret_cast<uintptr_t>(dst), d1 = d0 + tiles * 256 * dst_bits;
-  if (s0 < d1 && d0 < s1) return STQ_EINVAL;
-  DeviceGuard g(ctx->device);
-  if (!g.ok) return STQ_EHIP;
-  RepackArgs a;
-  a.src = static_cast<const uint32_t*>(src);
-  a.dst = static_cast<uint32_t*>(dst);
-  a.numel = numel;
-  a.n_tiles = static_cast<uint32_t>(tiles);
-  a.b_old = src_bits;
-  a.b_new = dst_bits;
-  build_repack_lut(state, static_cast<int>(src_bits), static_cast<int>(dst_bits), a.lut);
-  return launch_repack(a, stream) == 0 ? STQ_OK : STQ_EHIP;
+  // one job of stq_repack_many: the same checks, the same kernel
+  if (state != 0 && state != 1) return STQ_EINVAL;
+  stq_repack_job j;
+  j.numel = numel;
+  j.src_codes = src;
+  j.dst_codes = dst;
+  j.state = static_cast<uint8_t>(state);
+  j.src_bits = static_cast<uint8_t>(src_bits <= 255 ? src_bits : 255);
+  j.dst_bits = static_cast<uint8_t>(dst_bits <= 255 ? dst_bits : 255);
+  return stq_repack_many(ctx, &j, 1, block, stream);
 }
 
 int stq_repack_many(stq_ctx* ctx, const stq_repack_job* jobs, uint32_t n, uint32_t block, void* stream) {

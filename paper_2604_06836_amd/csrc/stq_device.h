@@ -58,13 +58,6 @@ struct ZeroArgs {
   uint32_t n_tiles, bm, bv, scales_per_tile;
 };
 
-struct RepackArgs {
-  const uint32_t* src; uint32_t* dst;
-  uint64_t numel;
-  uint32_t n_tiles, b_old, b_new;
-  uint8_t lut[256];
-};
-
 // One width change inside a batched re-pack launch.
 struct RepackJob {
   const uint32_t* src; uint32_t* dst;
@@ -88,7 +81,6 @@ struct RepackManyArgs {
 // stats: 0 none, 1 every statistic, 2 the gradient's only.
 int launch_step(const StepArgs& a, bool grad_bf16, int stats, int mode, uint32_t groups, void* stream);
 int launch_zero(const ZeroArgs& a, void* stream);
-int launch_repack(const RepackArgs& a, void* stream);
 int launch_repack_many(const RepackManyArgs& a, uint32_t groups, void* stream);
 int launch_grad_stats(const TensorDesc* desc, uint32_t n_tensors, uint32_t total_tiles, double* stats, bool grad_bf16,
                       uint32_t groups, void* stream);

@@ -45,41 +45,7 @@ __global__ __launch_bounds__(256) void zero_kernel(const ZeroArgs a) {
 }
 
 // --------------------------------------------------------------- re-pack kernel
-// Width change of one state: every code goes through a 256-entry table; pad codes stay 0.
-// One thread per (tile, lane) streams its b_old words into b_new words.
-__global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
-  __shared__ uint32_t lut[256];
-  lut[threadIdx.x] = a.lut[threadIdx.x];
-  __syncthreads();
-  const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
-  const uint64_t tile = gid >> 6;
-  const uint32_t lane = gid & 63;
-  if (tile >= a.n_tiles) return;
-  const uint32_t* src = a.src + tile * 64 * a.b_old + lane;
-  uint32_t* dst = a.dst + tile * 64 * a.b_new + lane;
-  const uint32_t mask = (1u << a.b_old) - 1u;
-  uint64_t in = 0, out = 0;
-  uint32_t in_bits = 0, out_bits = 0, ip = 0, op = 0;
-  for (uint32_t n = 0; n < 32; ++n) {
-    if (in_bits < a.b_old) {
-      in |= static_cast<uint64_t>(src[64 * ip++]) << in_bits;
-      in_bits += 32;
-    }
-    const uint32_t code = static_cast<uint32_t>(in) & mask;
-    in >>= a.b_old;
-    in_bits -= a.b_old;
-    const uint64_t idx = tile * kTile + 256 * (n >> 2) + 4 * lane + (n & 3);
-    const uint32_t c2 = idx < a.numel ? lut[code] : 0u;
-    out |= static_cast<uint64_t>(c2) << out_bits;
-    out_bits += a.b_new;
-    if (out_bits >= 32) {
-      dst[64 * op++] = static_cast<uint32_t>(out);
-      out >>= 32;
-      out_bits -= 32;
-    }
-  }
-}
-
+// Width change of stored states: every code goes through a 256-entry table; pad codes stay 0.
 // The lane's 32 codes of width B out of / into its B stream words; all shifts are compile-time.
 // Pointers that arrive through the job table are loaded from memory, so the compiler cannot see that they
 // are global; say so, to get global_load/global_store instead of flat accesses.
@@ -329,13 +295,6 @@ __global__ __launch_bounds__(256) void grad_stats_kernel(const TensorDesc* desc,
 int launch_zero(const ZeroArgs& a, void* stream) {
   const uint64_t threads = static_cast<uint64_t>(a.n_tiles) * 64;
   hipLaunchKernelGGL(zero_kernel, dim3(static_cast<uint32_t>((threads + 255) / 256)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), a);
-  return static_cast<int>(hipGetLastError());
-}
-
-int launch_repack(const RepackArgs& a, void* stream) {
-  const uint64_t threads = static_cast<uint64_t>(a.n_tiles) * 64;
-  hipLaunchKernelGGL(repack_kernel, dim3(static_cast<uint32_t>((threads + 255) / 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), a);
   return static_cast<int>(hipGetLastError());
 }
