@@ -21,8 +21,8 @@
  *     stq_step_transition and stq_grad_stats keep the tensor tables of the last four
  *     distinct argument sets on the device: a call whose tensors, plan and block size
  *     equal one of those, on the same stream, is one kernel launch and nothing else
- *     (no upload, no wait, no allocation).  Any other call, and every stq_repack_many,
- *     first uploads a small table from pinned host memory (sixteen staging slots
+ *     (no upload, no wait, no allocation).  Any other call, and every stq_repack and
+ *     stq_repack_many, first uploads a small table from pinned host memory (sixteen staging slots
  *     in turn; a slot whose last upload has not finished yet is waited for); such a
  *     call cannot be recorded into a HIP graph.  (The step number reaches the kernel as launch arguments, so a
  *     recorded launch repeats its own step.)  stq_engine_step is asynchronous too; with
@@ -226,7 +226,8 @@ int stq_stats(stq_ctx* ctx, stq_layer_stats* out, uint32_t n, void* hip_stream);
  * Map changed the layer's width.  state: 0 = first moment, 1 = second moment.
  * Code-domain conversion: the new code is the one the dst_bits quantizer gives
  * the old code's value in a block of scale 1; the scales array is shared by
- * both widths and is not touched.  src and dst must not overlap. */
+ * both widths and is not touched.  src and dst must not overlap.  The same as
+ * stq_repack_many with one job. */
 int stq_repack(stq_ctx* ctx, uint64_t numel, uint32_t block, int state,
                const void* src_codes, uint32_t src_bits,
                void* dst_codes, uint32_t dst_bits, void* hip_stream);
