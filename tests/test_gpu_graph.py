@@ -24,8 +24,8 @@ def same(a, b, tag):
             assert np.array_equal(u.view(np.uint32), v.view(np.uint32)), f"{tag}: tensor {l} {name}"
 
 
-@pytest.mark.parametrize("tickets", [False, True])
-def test_recorded_step_replays_like_the_eager_step(tickets):
+@pytest.mark.parametrize("tickets,kind", [(False, "grad"), (True, "grad"), (True, True)])
+def test_recorded_step_replays_like_the_eager_step(tickets, kind):
     w = configs.Workload(85, "graph", [("a", 30 * 2048 + 99), ("b", 4097), ("c", 12 * 2048)], 128, "bf16", 1,
                          "normal_per_tensor")
     plan = [(5, 4), (8, 3), (4, 6)]
@@ -41,7 +41,7 @@ def test_recorded_step_replays_like_the_eager_step(tickets):
                 dm.step(1)              # uploads the tensor table on this stream
             side.synchronize()
             same(snapshot(ref), snapshot(rec), "before recording")
-            hp = hparams(w, 2, "grad")  # the recorded step also gathers the gradient's statistics
+            hp = hparams(w, 2, kind)    # the recorded step also gathers statistics: the gradient's, or all
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=side):
                 rec.ctx.step(rec.tensors, rec.cplan, hp, side.cuda_stream)
@@ -58,6 +58,8 @@ def test_recorded_step_replays_like_the_eager_step(tickets):
             # (the recorded launches are not counted by the host: their statistics are read as one step's)
             for l in range(3):
                 assert abs(a[l].g_sq_sum - b[l].g_sq_sum) <= 1e-12 * a[l].g_sq_sum and a[l].g_absmax == b[l].g_absmax
+                assert abs(a[l].m_sq_sum - b[l].m_sq_sum) <= 1e-6 * a[l].m_sq_sum and a[l].v_absmax == b[l].v_absmax
+                assert (a[l].m_sq_sum > 0) == (kind is True)
     finally:
         for c in ctxs:
             c.close()
