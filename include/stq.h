@@ -150,7 +150,8 @@ int stq_init(stq_ctx** out, int device, uint32_t max_tensors);
  * runs of neighbouring tiles from a counter in device memory and their waves work on them in step, so the
  * chip sweeps every array front to back inside one compact window -- worth 10-15 % of bandwidth on
  * multi-gigabyte workloads, a loss on small ones, where each wave keeps walking its own stripes.
- * 0 restores the default (about 0.3 G elements); UINT64_MAX never uses tickets.  Host only. */
+ * Steps that gather statistics switch at a third of the value.  0 restores the default (about 0.3 G
+ * elements); UINT64_MAX never uses tickets.  Host only. */
 int stq_set_schedule(stq_ctx* ctx, uint64_t ticket_min_tiles);
 
 /* Synchronise the device and free everything the context owns. */
