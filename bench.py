@@ -333,6 +333,8 @@ def main():
         tr = json.load(open(traffic_file)).get(w.name + ("-engine" if args.transition == "engine" else ("-engine-alg1" if use_engine else "")))
         if tr and tr.get("kernel_source_sha256") == src_hash:
             out["roofline"]["traffic"] = tr["hbm_bytes_per_launch"]
+            # the same counters over this run's kernel duration: HBM GB/s as the counters see it
+            out["roofline"]["traffic_GBps"] = tr["hbm_bytes_per_launch"] / (k_avg_ms * 1e-3) / 1e9
             if "valu_insts_per_param" in tr:
                 # The second roof of this kernel: vector instructions.  One fp32 VALU instruction per lane and
                 # cycle on 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz (the published 157.3 TFLOP/s counts packed
