@@ -76,8 +76,9 @@ def assert_stats_close(g, o, tag):
             # the gradient's sums are taken in fp64 from the first addition: only the order differs
             assert abs(a - b) <= 1e-12 * scale, f"{tag} {name}: {a} vs {b}"
             continue
-        # the kernel sums each lane's elements of up to 16 tiles in fp32 before widening to fp64, so
-        # terms below the smallest normal fp32 (2^-126) lose bits: absolute floor of count * 2^-126
+        # the kernel adds the moments' terms in fp32 (a lane's 8 elements of a quarter, then eight lanes, then
+        # the quarters of up to 16 tiles) before widening to fp64, so terms below the smallest normal fp32
+        # (2^-126) lose bits: absolute floor of count * 2^-126
         assert abs(a - b) <= 1e-5 * scale + o.count * 1.2e-38, f"{tag} {name}: {a} vs {b}"
     for name in ("g_absmax", "m_absmax", "v_absmax"):
         assert getattr(g, name) == getattr(o, name), f"{tag} {name}"
